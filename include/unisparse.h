@@ -1,0 +1,166 @@
+/*
+ * unisparse.h -- C ABI of the UniSparse hot path for AMD MI355X (gfx950).
+ *
+ * UniSparse (arXiv 2512.14082) builds a block-sparse attention mask M from a cheap proxy
+ * computed on "composite tokens" (average-pooled queries and keys) and then runs
+ * block-sparse attention over the selected (query block, key block) pairs:
+ *
+ *   Alg. 1 step 1  sequence / head average pooling                     Eq. (1), Eq. (2)
+ *   Alg. 1 step 2  compressed logits Q~ K~^T / sqrt(d_k), row softmax  Sec. 4.3
+ *   Alg. 1 step 3  block aggregation Score(i, j)                       Eq. (3), Eq. (4)
+ *   Alg. 1 step 4  causal cut + Top-P selection (or a fixed budget)    Eq. (5)
+ *   Alg. 1 step 5  block-sparse attention with mask M                  Sec. 2.2
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ * - All tensor pointers are DEVICE pointers unless a comment says HOST.  The caller owns
+ *   every buffer (inputs, outputs, workspace).  The library allocates no device memory,
+ *   never synchronises the device or a stream, and enqueues work only on the stream given.
+ * - Element type of Q, K, V, O and of the composite tokens is bf16 (2 bytes).  head_dim = 128.
+ * - A problem is a packed batch of B sequences ("varlen"): tokens of all sequences are
+ *   concatenated along the token axis, sequence b owning tokens [cu_seqlens[b], cu_seqlens[b+1]).
+ *   Every sequence length must be a multiple of block_size.  Sequences never interact.
+ * - Grouped-query attention: query head h uses key/value head h / (n_heads_q / n_heads_kv).
+ * - Query-block rows are numbered over the packed batch: row r = (blocks of earlier sequences)
+ *   + local block index i.  NQ = total_tokens / block_size rows, NK = max_b L_b / block_size.
+ * - Mask layout: uint64 M[n_heads_q][NQ][W], W = ceil(NK / 64).  Bit (j % 64) of word j / 64 of
+ *   row r says whether query block r attends key block j *of its own sequence*.  Bits with
+ *   j > i under causality and bits with j >= N_b are always written as 0 by build_mask and
+ *   are ignored (treated as 0) by sparse_attn.
+ * - Errors: every call validates its arguments on the host before launching anything and
+ *   returns a status; on error no kernel is launched and no output is touched.  Launch
+ *   failures reported by HIP map to UNISPARSE_ERR_HIP.
+ * - stream arguments are hipStream_t values passed as void* (NULL = the null stream).
+ */
+#ifndef UNISPARSE_H
+#define UNISPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define UNISPARSE_MAX_SEQS 16      /* sequences per packed batch */
+#define UNISPARSE_HEAD_DIM 128
+#define UNISPARSE_MAX_BLOCKS_PER_SEQ 4096   /* NK limit (selection sorts one row in LDS) */
+
+typedef struct unisparse_ctx unisparse_ctx;   /* opaque; caches device properties only */
+
+typedef enum {
+    UNISPARSE_OK = 0,
+    UNISPARSE_ERR_NULL = 1,          /* a required pointer is NULL */
+    UNISPARSE_ERR_SHAPE = 2,         /* lengths not multiples of block_size, c not dividing it, head counts ... */
+    UNISPARSE_ERR_PARAM = 3,         /* threshold / budget outside (0, 1], unknown mode ... */
+    UNISPARSE_ERR_UNSUPPORTED = 4,   /* valid request this build has no kernel for */
+    UNISPARSE_ERR_WORKSPACE = 5,     /* workspace smaller than unisparse_workspace_bytes() */
+    UNISPARSE_ERR_HIP = 6            /* HIP runtime reported an error */
+} unisparse_status;
+
+/* Problem geometry.  cu_seqlens is a HOST pointer to num_seqs + 1 int32 (cu[0] = 0); it is read
+ * during the call and not retained. */
+typedef struct {
+    int32_t num_seqs;                /* B, 1 .. UNISPARSE_MAX_SEQS */
+    const int32_t *cu_seqlens;       /* HOST */
+    int32_t n_heads_q;               /* H */
+    int32_t n_heads_kv;              /* H_kv, divides H */
+    int32_t head_dim;                /* must be 128 */
+    int32_t block_size;              /* S: 64 or 128 */
+    int32_t causal;                  /* 0 / 1 */
+    float softmax_scale;             /* 0 -> 1 / sqrt(head_dim) */
+} unisparse_problem;
+
+/* A [tokens, heads, head_dim] view with arbitrary token / head strides (in elements); the last
+ * dimension is contiguous and 16-byte aligned.  Covers both token-major and head-major storage. */
+typedef struct {
+    void *ptr;                       /* DEVICE, bf16 */
+    int64_t stride_tok;
+    int64_t stride_head;
+} unisparse_tensor;
+
+#define UNISPARSE_TOP_P 0            /* cumulative-score threshold, Eq. (5) */
+#define UNISPARSE_TOP_K 1            /* fixed budget: keep max(1, ceil(f * n_valid)) blocks per row */
+
+/* Selection parameters (the inputs of Alg. 1 besides Q, K, V and S). */
+typedef struct {
+    int32_t c_q, c_k;                /* sequence compression factors; block_size / c must be 8, 16 or 32 */
+    int32_t c_h;                     /* head compression factor; must divide H.  Groups of c_h query heads
+                                        share one mask (Eq. (2) and the broadcast of Alg. 1) */
+    int32_t mode;                    /* UNISPARSE_TOP_P or UNISPARSE_TOP_K */
+    double threshold;                /* P in (0, 1]; P >= 1 keeps every valid block */
+    double budget_frac;              /* f in (0, 1] */
+} unisparse_select;
+
+unisparse_status unisparse_create(unisparse_ctx **ctx, int device);
+void unisparse_destroy(unisparse_ctx *ctx);
+const char *unisparse_status_string(unisparse_status s);
+
+/* Sizes the caller needs for its allocations.  All return 0 for an invalid problem. */
+size_t unisparse_mask_row_words(const unisparse_problem *p);             /* W                         */
+size_t unisparse_mask_words(const unisparse_problem *p);                 /* H * NQ * W  (uint64)      */
+size_t unisparse_score_elems(const unisparse_problem *p, const unisparse_select *s); /* (H/c_h)*NQ*NK floats */
+size_t unisparse_workspace_bytes(const unisparse_problem *p, const unisparse_select *s);
+
+/*
+ * Sequence-level average pooling, Eq. (1): out[h][t'][:] = bf16( (1/c) * sum_{m<c} x[t'c + m][h][:] ),
+ * fp32 sum in token order, one rounding to bf16 (nearest even).
+ *   x       : [total_tokens, n_heads, 128] view
+ *   out     : DEVICE bf16 [n_heads][total_tokens / c][128], contiguous
+ * total_tokens must be a multiple of c (windows then never straddle sequences whose lengths are
+ * multiples of c).
+ */
+unisparse_status unisparse_avgpool_seq(unisparse_ctx *ctx, unisparse_tensor x, int32_t n_heads,
+                                       int64_t total_tokens, int32_t c, void *out, void *stream);
+
+/*
+ * Alg. 1 steps 1-4: composite tokens, compressed softmax scores, block aggregation, selection.
+ *   Q : [T, H, 128] view, K : [T, H_kv, 128] view
+ *   workspace : DEVICE scratch of at least unisparse_workspace_bytes() bytes, 256-byte aligned
+ *   M     : out, uint64 [H][NQ][W]
+ *   score : out, optional (may be NULL), float [H / c_h][NQ][NK]; Score(i, j) of Eq. (3) for valid j,
+ *           0 elsewhere.  When NULL the scores live in the workspace.
+ * Causal problems exclude, inside the compressed softmax, composite keys whose window starts after
+ * the last token of the composite query's window, and drop key blocks j > i before selection.
+ */
+unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_problem *p,
+                                      const unisparse_select *s, unisparse_tensor Q, unisparse_tensor K,
+                                      void *workspace, size_t workspace_bytes, uint64_t *M, float *score,
+                                      void *stream);
+
+/*
+ * Selection only (Alg. 1 step 4) on caller-provided scores, e.g. to re-select with another threshold.
+ *   score : float [H / c_h][NQ][NK] (read; entries outside a row's valid set are overwritten with 0)
+ */
+unisparse_status unisparse_select_blocks(unisparse_ctx *ctx, const unisparse_problem *p,
+                                         const unisparse_select *s, float *score, uint64_t *M, void *stream);
+
+/*
+ * Alg. 1 step 5 / Sec. 2.2: O = softmax(Q K^T * scale + M~) V over the selected blocks only, with
+ * token-level causality inside the diagonal block.
+ *   Q, O : [T, H, 128] views;  K, V : [T, H_kv, 128] views;  M as above
+ *   lse  : optional (may be NULL), float [H][T]: natural-log sum of exponentials of the visible logits
+ * A query row whose mask row is empty gets O = 0 and lse = -inf.
+ */
+unisparse_status unisparse_sparse_attn(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor Q,
+                                       unisparse_tensor K, unisparse_tensor V, const uint64_t *M,
+                                       unisparse_tensor O, float *lse, void *stream);
+
+/* Dense attention (Sec. 2.1): the same kernel visiting every valid block.  The speedup baseline. */
+unisparse_status unisparse_full_attn(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor Q,
+                                     unisparse_tensor K, unisparse_tensor V, unisparse_tensor O, float *lse,
+                                     void *stream);
+
+/*
+ * The paper's one-call interface (Sec. 5): build_mask followed by sparse_attn on the same stream.
+ *   M : scratch/out uint64 [H][NQ][W] (the mask that was used, left for inspection)
+ */
+unisparse_status unisparse_attn(unisparse_ctx *ctx, const unisparse_problem *p, const unisparse_select *s,
+                                unisparse_tensor Q, unisparse_tensor K, unisparse_tensor V, void *workspace,
+                                size_t workspace_bytes, uint64_t *M, unisparse_tensor O, float *lse,
+                                void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UNISPARSE_H */

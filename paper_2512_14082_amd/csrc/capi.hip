@@ -1,0 +1,356 @@
+// C ABI of the UniSparse library: argument validation, workspace carving, kernel sequencing.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "common.h"
+
+struct unisparse_ctx {
+    int device;
+    int n_cu;
+    size_t lds_per_block;
+};
+
+namespace {
+
+using namespace us;
+
+struct Geom {
+    SeqTable st;
+    int64_t T;
+    int NQ, NK, W;
+};
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+unisparse_status check_problem(const unisparse_problem *p, Geom *g)
+{
+    if (p == nullptr || p->cu_seqlens == nullptr) return UNISPARSE_ERR_NULL;
+    if (p->num_seqs < 1 || p->num_seqs > UNISPARSE_MAX_SEQS) return UNISPARSE_ERR_SHAPE;
+    if (p->head_dim != UNISPARSE_HEAD_DIM) return UNISPARSE_ERR_UNSUPPORTED;
+    if (p->block_size != 64 && p->block_size != 128) return UNISPARSE_ERR_UNSUPPORTED;
+    if (p->n_heads_q < 1 || p->n_heads_kv < 1 || p->n_heads_q % p->n_heads_kv != 0) return UNISPARSE_ERR_SHAPE;
+    if (!(p->softmax_scale >= 0.0f) || std::isinf(p->softmax_scale)) return UNISPARSE_ERR_PARAM;
+    if (p->cu_seqlens[0] != 0) return UNISPARSE_ERR_SHAPE;
+    std::memset(&g->st, 0, sizeof(g->st));
+    g->st.num_seqs = p->num_seqs;
+    int64_t nq = 0, nk = 0;
+    for (int b = 0; b < p->num_seqs; ++b) {
+        int64_t len = (int64_t)p->cu_seqlens[b + 1] - (int64_t)p->cu_seqlens[b];
+        if (len < 0 || len % p->block_size != 0) return UNISPARSE_ERR_SHAPE;
+        g->st.cu_tok[b] = p->cu_seqlens[b];
+        nq += len / p->block_size;
+        if (len / p->block_size > nk) nk = len / p->block_size;
+    }
+    g->st.cu_tok[p->num_seqs] = p->cu_seqlens[p->num_seqs];
+    if (nk > UNISPARSE_MAX_BLOCKS_PER_SEQ) return UNISPARSE_ERR_UNSUPPORTED;
+    g->T = p->cu_seqlens[p->num_seqs];
+    g->NQ = (int)nq;
+    g->NK = (int)nk;
+    g->W = (int)((nk + 63) / 64);
+    return UNISPARSE_OK;
+}
+
+// Compressed head geometry for head-level pooling (Eq. (2)) under grouped-query attention.
+struct HeadGeom {
+    int Hc;        // compressed query heads
+    int Hkc;       // key heads the compressed queries attend
+    int kpool;     // key heads averaged into one (1 = none)
+};
+
+unisparse_status check_select(const unisparse_problem *p, const unisparse_select *s, HeadGeom *hg)
+{
+    if (s == nullptr) return UNISPARSE_ERR_NULL;
+    if (s->c_q < 1 || s->c_k < 1 || s->c_h < 1) return UNISPARSE_ERR_PARAM;
+    if (p->block_size % s->c_q != 0 || p->block_size % s->c_k != 0) return UNISPARSE_ERR_SHAPE;
+    int nq = p->block_size / s->c_q, nk = p->block_size / s->c_k;
+    auto ok = [](int n) { return n == 8 || n == 16 || n == 32; };
+    if (!ok(nq) || !ok(nk)) return UNISPARSE_ERR_UNSUPPORTED;
+    if (s->mode != UNISPARSE_TOP_P && s->mode != UNISPARSE_TOP_K) return UNISPARSE_ERR_PARAM;
+    if (s->mode == UNISPARSE_TOP_P && !(s->threshold > 0.0 && s->threshold <= 1.0)) return UNISPARSE_ERR_PARAM;
+    if (s->mode == UNISPARSE_TOP_K && !(s->budget_frac > 0.0 && s->budget_frac <= 1.0)) return UNISPARSE_ERR_PARAM;
+    if (p->n_heads_q % s->c_h != 0) return UNISPARSE_ERR_SHAPE;
+    const int G = p->n_heads_q / p->n_heads_kv;
+    hg->Hc = p->n_heads_q / s->c_h;
+    if (G % s->c_h == 0) {                 // groups of c_h heads stay inside one key head
+        hg->Hkc = p->n_heads_kv;
+        hg->kpool = 1;
+    } else if (s->c_h % G == 0) {          // a group spans c_h / G whole key heads
+        hg->kpool = s->c_h / G;
+        hg->Hkc = p->n_heads_kv / hg->kpool;
+    } else {
+        return UNISPARSE_ERR_UNSUPPORTED;
+    }
+    return UNISPARSE_OK;
+}
+
+unisparse_status check_tensor(const unisparse_tensor &t)
+{
+    if (t.ptr == nullptr) return UNISPARSE_ERR_NULL;
+    if (((uintptr_t)t.ptr & 15) != 0 || t.stride_tok % 8 != 0 || t.stride_head % 8 != 0) return UNISPARSE_ERR_SHAPE;
+    if (t.stride_tok < UNISPARSE_HEAD_DIM && t.stride_head < UNISPARSE_HEAD_DIM) return UNISPARSE_ERR_SHAPE;
+    return UNISPARSE_OK;
+}
+
+inline TensorView view(const unisparse_tensor &t)
+{
+    return TensorView{reinterpret_cast<const bf16_t *>(t.ptr), t.stride_tok, t.stride_head};
+}
+
+inline float scale_log2(const unisparse_problem *p)
+{
+    float sc = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / std::sqrt((float)p->head_dim);
+    return sc * kLog2e;
+}
+
+struct WsLayout {
+    size_t qt, kt, qth, kth, score, total;
+};
+
+WsLayout carve(const unisparse_problem *p, const unisparse_select *s, const Geom &g, const HeadGeom &hg,
+               bool need_score)
+{
+    WsLayout w;
+    size_t off = 0;
+    const size_t row = (size_t)UNISPARSE_HEAD_DIM * 2;
+    w.qt = off; off += align256((size_t)p->n_heads_q * (g.T / s->c_q) * row);
+    w.kt = off; off += align256((size_t)p->n_heads_kv * (g.T / s->c_k) * row);
+    w.qth = off; if (s->c_h > 1) off += align256((size_t)hg.Hc * (g.T / s->c_q) * row);
+    w.kth = off; if (hg.kpool > 1) off += align256((size_t)hg.Hkc * (g.T / s->c_k) * row);
+    w.score = off; if (need_score) off += align256((size_t)hg.Hc * g.NQ * g.NK * sizeof(float));
+    w.total = off;
+    return w;
+}
+
+unisparse_status select_impl(const unisparse_problem *p, const unisparse_select *s, const Geom &g,
+                             const HeadGeom &hg, float *score, uint64_t *M, hipStream_t stream)
+{
+    SelectArgs sa;
+    sa.score = score;
+    sa.mask = M;
+    sa.st = g.st;
+    sa.n_heads_c = hg.Hc;
+    sa.c_h = s->c_h;
+    sa.S = p->block_size;
+    sa.causal = p->causal;
+    sa.NQ = g.NQ;
+    sa.NK = g.NK;
+    sa.W = g.W;
+    sa.mode = s->mode;
+    sa.param = s->mode == UNISPARSE_TOP_P ? s->threshold : s->budget_frac;
+    return launch_select(sa, stream) == hipSuccess ? UNISPARSE_OK : UNISPARSE_ERR_HIP;
+}
+
+unisparse_status attn_impl(const unisparse_problem *p, const Geom &g, unisparse_tensor Q, unisparse_tensor K,
+                           unisparse_tensor V, const uint64_t *M, unisparse_tensor O, float *lse,
+                           hipStream_t stream)
+{
+    unisparse_status st;
+    if ((st = check_tensor(Q)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(K)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(V)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(O)) != UNISPARSE_OK) return st;
+    AttnArgs a;
+    a.q = view(Q);
+    a.k = view(K);
+    a.v = view(V);
+    a.o = reinterpret_cast<bf16_t *>(O.ptr);
+    a.o_stride_tok = O.stride_tok;
+    a.o_stride_head = O.stride_head;
+    a.mask = M;
+    a.lse = lse;
+    a.st = g.st;
+    a.n_heads_q = p->n_heads_q;
+    a.n_heads_kv = p->n_heads_kv;
+    a.S = p->block_size;
+    a.causal = p->causal;
+    a.NQ = g.NQ;
+    a.W = g.W;
+    a.total_tokens = g.T;
+    a.scale_log2 = scale_log2(p);
+    return launch_attention(a, stream) == hipSuccess ? UNISPARSE_OK : UNISPARSE_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+unisparse_status unisparse_create(unisparse_ctx **ctx, int device)
+{
+    if (ctx == nullptr) return UNISPARSE_ERR_NULL;
+    *ctx = nullptr;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return UNISPARSE_ERR_HIP;
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return UNISPARSE_ERR_UNSUPPORTED;
+    unisparse_ctx *c = new (std::nothrow) unisparse_ctx;
+    if (c == nullptr) return UNISPARSE_ERR_HIP;
+    c->device = device;
+    c->n_cu = prop.multiProcessorCount;
+    c->lds_per_block = prop.sharedMemPerBlock;
+    *ctx = c;
+    return UNISPARSE_OK;
+}
+
+void unisparse_destroy(unisparse_ctx *ctx) { delete ctx; }
+
+const char *unisparse_status_string(unisparse_status s)
+{
+    switch (s) {
+        case UNISPARSE_OK: return "ok";
+        case UNISPARSE_ERR_NULL: return "null pointer";
+        case UNISPARSE_ERR_SHAPE: return "invalid shape";
+        case UNISPARSE_ERR_PARAM: return "invalid parameter";
+        case UNISPARSE_ERR_UNSUPPORTED: return "unsupported configuration";
+        case UNISPARSE_ERR_WORKSPACE: return "workspace too small";
+        case UNISPARSE_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+size_t unisparse_mask_row_words(const unisparse_problem *p)
+{
+    Geom g;
+    return check_problem(p, &g) == UNISPARSE_OK ? (size_t)g.W : 0;
+}
+
+size_t unisparse_mask_words(const unisparse_problem *p)
+{
+    Geom g;
+    return check_problem(p, &g) == UNISPARSE_OK ? (size_t)p->n_heads_q * g.NQ * g.W : 0;
+}
+
+size_t unisparse_score_elems(const unisparse_problem *p, const unisparse_select *s)
+{
+    Geom g;
+    HeadGeom hg;
+    if (check_problem(p, &g) != UNISPARSE_OK || check_select(p, s, &hg) != UNISPARSE_OK) return 0;
+    return (size_t)hg.Hc * g.NQ * g.NK;
+}
+
+size_t unisparse_workspace_bytes(const unisparse_problem *p, const unisparse_select *s)
+{
+    Geom g;
+    HeadGeom hg;
+    if (check_problem(p, &g) != UNISPARSE_OK || check_select(p, s, &hg) != UNISPARSE_OK) return 0;
+    return carve(p, s, g, hg, true).total + 256;
+}
+
+unisparse_status unisparse_avgpool_seq(unisparse_ctx *ctx, unisparse_tensor x, int32_t n_heads, int64_t total_tokens,
+                                       int32_t c, void *out, void *stream)
+{
+    if (ctx == nullptr || out == nullptr) return UNISPARSE_ERR_NULL;
+    unisparse_status st = check_tensor(x);
+    if (st != UNISPARSE_OK) return st;
+    if (n_heads < 1 || total_tokens < 0 || c < 1 || total_tokens % c != 0) return UNISPARSE_ERR_SHAPE;
+    if (((uintptr_t)out & 15) != 0) return UNISPARSE_ERR_SHAPE;
+    hipError_t e = launch_avgpool_seq(view(x), n_heads, total_tokens, c, reinterpret_cast<bf16_t *>(out),
+                                      (hipStream_t)stream);
+    return e == hipSuccess ? UNISPARSE_OK : UNISPARSE_ERR_HIP;
+}
+
+unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_problem *p, const unisparse_select *s,
+                                      unisparse_tensor Q, unisparse_tensor K, void *workspace,
+                                      size_t workspace_bytes, uint64_t *M, float *score, void *stream_)
+{
+    if (ctx == nullptr || M == nullptr || workspace == nullptr) return UNISPARSE_ERR_NULL;
+    Geom g;
+    HeadGeom hg;
+    unisparse_status st;
+    if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
+    if ((st = check_select(p, s, &hg)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(Q)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(K)) != UNISPARSE_OK) return st;
+    // composite windows must not straddle sequences: guaranteed because c divides S and S divides every length
+    const WsLayout w = carve(p, s, g, hg, score == nullptr);
+    unsigned char *base = reinterpret_cast<unsigned char *>(align256((size_t)(uintptr_t)workspace));
+    const size_t lead = (size_t)(base - reinterpret_cast<unsigned char *>(workspace));
+    if (workspace_bytes < w.total + lead) return UNISPARSE_ERR_WORKSPACE;
+    if (g.T == 0) return UNISPARSE_OK;
+    hipStream_t stream = (hipStream_t)stream_;
+
+    bf16_t *qt = reinterpret_cast<bf16_t *>(base + w.qt);
+    bf16_t *kt = reinterpret_cast<bf16_t *>(base + w.kt);
+    if (launch_avgpool_seq(view(Q), p->n_heads_q, g.T, s->c_q, qt, stream) != hipSuccess) return UNISPARSE_ERR_HIP;
+    if (launch_avgpool_seq(view(K), p->n_heads_kv, g.T, s->c_k, kt, stream) != hipSuccess) return UNISPARSE_ERR_HIP;
+    if (s->c_h > 1) {
+        bf16_t *qth = reinterpret_cast<bf16_t *>(base + w.qth);
+        if (launch_avgpool_head(qt, p->n_heads_q, g.T / s->c_q, s->c_h, qth, stream) != hipSuccess)
+            return UNISPARSE_ERR_HIP;
+        qt = qth;
+        if (hg.kpool > 1) {
+            bf16_t *kth = reinterpret_cast<bf16_t *>(base + w.kth);
+            if (launch_avgpool_head(kt, p->n_heads_kv, g.T / s->c_k, hg.kpool, kth, stream) != hipSuccess)
+                return UNISPARSE_ERR_HIP;
+            kt = kth;
+        }
+    }
+    float *sc = score != nullptr ? score : reinterpret_cast<float *>(base + w.score);
+    ProxyArgs pa;
+    pa.qt = qt;
+    pa.kt = kt;
+    pa.score = sc;
+    pa.st = g.st;
+    pa.n_heads_q = hg.Hc;
+    pa.n_heads_kv = hg.Hkc;
+    pa.S = p->block_size;
+    pa.c_q = s->c_q;
+    pa.c_k = s->c_k;
+    pa.causal = p->causal;
+    pa.NQ = g.NQ;
+    pa.NK = g.NK;
+    pa.scale_log2 = scale_log2(p);
+    if (launch_proxy_scores(pa, stream) != hipSuccess) return UNISPARSE_ERR_HIP;
+    return select_impl(p, s, g, hg, sc, M, stream);
+}
+
+unisparse_status unisparse_select_blocks(unisparse_ctx *ctx, const unisparse_problem *p, const unisparse_select *s,
+                                         float *score, uint64_t *M, void *stream)
+{
+    if (ctx == nullptr || score == nullptr || M == nullptr) return UNISPARSE_ERR_NULL;
+    Geom g;
+    HeadGeom hg;
+    unisparse_status st;
+    if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
+    if ((st = check_select(p, s, &hg)) != UNISPARSE_OK) return st;
+    if (g.T == 0) return UNISPARSE_OK;
+    return select_impl(p, s, g, hg, score, M, (hipStream_t)stream);
+}
+
+unisparse_status unisparse_sparse_attn(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor Q,
+                                       unisparse_tensor K, unisparse_tensor V, const uint64_t *M,
+                                       unisparse_tensor O, float *lse, void *stream)
+{
+    if (ctx == nullptr || M == nullptr) return UNISPARSE_ERR_NULL;
+    Geom g;
+    unisparse_status st;
+    if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
+    if (g.T == 0) return check_tensor(Q);
+    return attn_impl(p, g, Q, K, V, M, O, lse, (hipStream_t)stream);
+}
+
+unisparse_status unisparse_full_attn(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor Q,
+                                     unisparse_tensor K, unisparse_tensor V, unisparse_tensor O, float *lse,
+                                     void *stream)
+{
+    if (ctx == nullptr) return UNISPARSE_ERR_NULL;
+    Geom g;
+    unisparse_status st;
+    if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
+    if (g.T == 0) return check_tensor(Q);
+    return attn_impl(p, g, Q, K, V, nullptr, O, lse, (hipStream_t)stream);
+}
+
+unisparse_status unisparse_attn(unisparse_ctx *ctx, const unisparse_problem *p, const unisparse_select *s,
+                                unisparse_tensor Q, unisparse_tensor K, unisparse_tensor V, void *workspace,
+                                size_t workspace_bytes, uint64_t *M, unisparse_tensor O, float *lse, void *stream)
+{
+    unisparse_status st;
+    if ((st = check_tensor(V)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(O)) != UNISPARSE_OK) return st;
+    st = unisparse_build_mask(ctx, p, s, Q, K, workspace, workspace_bytes, M, nullptr, stream);
+    if (st != UNISPARSE_OK) return st;
+    return unisparse_sparse_attn(ctx, p, Q, K, V, M, O, lse, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,125 @@
+// Shared declarations of the UniSparse HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "unisparse.h"
+
+namespace us {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kHeadDim = UNISPARSE_HEAD_DIM;
+constexpr int kMaxSeqs = UNISPARSE_MAX_SEQS;
+constexpr int kNumXcd = 8;              // MI355X: 8 accelerator dies, workgroups are dealt round-robin to them
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Packed-batch geometry passed to kernels by value.
+struct SeqTable {
+    int32_t num_seqs;
+    int32_t cu_tok[kMaxSeqs + 1];       // token offsets, cu_tok[num_seqs] = total tokens
+};
+
+struct TensorView {
+    const bf16_t *ptr;
+    int64_t stride_tok;
+    int64_t stride_head;
+};
+
+// Packed query-block row -> (sequence, local block index, blocks in that sequence).
+__device__ __forceinline__ void locate_row(const SeqTable &st, int S, int row, int &seq, int &local, int &nblk)
+{
+    seq = 0;
+    int base = 0;
+#pragma unroll 1
+    for (int b = 0; b < st.num_seqs; ++b) {
+        int nb = (st.cu_tok[b + 1] - st.cu_tok[b]) / S;
+        if (row < base + nb) { seq = b; local = row - base; nblk = nb; return; }
+        base += nb;
+    }
+    seq = st.num_seqs - 1; local = 0; nblk = 0;   // not reached for valid rows
+}
+
+// Workgroup ids are dealt round-robin over the 8 XCDs (each with a private L2).  This maps the
+// hardware id to a virtual id such that consecutive virtual ids share an XCD.
+__device__ __forceinline__ int xcd_contiguous_id(int bid, int nblocks)
+{
+    int xcd = bid % kNumXcd, idx = bid / kNumXcd;
+    int low = nblocks / kNumXcd, rem = nblocks % kNumXcd;
+    return xcd * low + (xcd < rem ? xcd : rem) + idx;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Exchange between lane l and lane l ^ 32.
+__device__ __forceinline__ float swap_half(float x)
+{
+    return __shfl_xor(x, 32, 64);
+}
+
+// float -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+struct Launch {
+    hipStream_t stream;
+};
+
+// ---- kernel launchers (defined one per .hip file) ------------------------------------------
+hipError_t launch_avgpool_seq(const TensorView &x, int n_heads, int64_t total_tokens, int c, bf16_t *out,
+                              hipStream_t stream);
+hipError_t launch_avgpool_head(const bf16_t *x, int n_heads_in, int64_t tokens, int c_h, bf16_t *out,
+                               hipStream_t stream);
+
+struct ProxyArgs {
+    const bf16_t *qt;        // [Hc][Tq][128] composite queries (Tq = T / c_q)
+    const bf16_t *kt;        // [Hkc][Tk][128] composite keys
+    float *score;            // [Hc][NQ][NK]
+    SeqTable st;
+    int32_t n_heads_q, n_heads_kv;   // (compressed) head counts
+    int32_t S, c_q, c_k;
+    int32_t causal;
+    int32_t NQ, NK;
+    float scale_log2;        // softmax scale * log2(e)
+};
+hipError_t launch_proxy_scores(const ProxyArgs &a, hipStream_t stream);
+
+struct SelectArgs {
+    float *score;            // [Hc][NQ][NK]
+    uint64_t *mask;          // [Hc * c_h][NQ][W]
+    SeqTable st;
+    int32_t n_heads_c;       // compressed heads
+    int32_t c_h;
+    int32_t S, causal, NQ, NK, W;
+    int32_t mode;
+    double param;
+};
+hipError_t launch_select(const SelectArgs &a, hipStream_t stream);
+
+struct AttnArgs {
+    TensorView q, k, v;
+    bf16_t *o;
+    int64_t o_stride_tok, o_stride_head;
+    const uint64_t *mask;    // NULL = dense
+    float *lse;              // optional [H][T]
+    SeqTable st;
+    int32_t n_heads_q, n_heads_kv;
+    int32_t S, causal, NQ, W;
+    int64_t total_tokens;
+    float scale_log2;
+};
+hipError_t launch_attention(const AttnArgs &a, hipStream_t stream);
+
+}  // namespace us

@@ -1,0 +1,126 @@
+// Composite tokens: sequence-level (Eq. (1)) and head-level (Eq. (2)) average pooling.
+//
+// HBM-bound streaming kernels.  One thread owns 8 consecutive channels (16 bytes) of one composite
+// token, so the 16 threads of a token read one coalesced 256-byte row per source token.  The sum is
+// an fp32 sum in token (head) order followed by one fp32 division and one round-to-nearest-even to
+// bf16, which is bit-for-bit what a bf16 average pool defines.
+#include "common.h"
+
+namespace us {
+
+__device__ __forceinline__ void unpack8(const u32x4 &w, float *f)
+{
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f[2 * e] = __uint_as_float(w[e] << 16);
+        f[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+}
+
+__device__ __forceinline__ u32x4 pack8_rne(const float *f)
+{
+    u32x4 w;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = f32_to_bf16_rne(f[2 * e]) | (f32_to_bf16_rne(f[2 * e + 1]) << 16);
+    return w;
+}
+
+template <int C>
+__global__ __launch_bounds__(256) void avgpool_seq_kernel(const bf16_t *__restrict__ x, int64_t stride_tok,
+                                                          int64_t stride_head, int64_t tokens_out, int c_rt,
+                                                          int64_t n_items, bf16_t *__restrict__ out)
+{
+    const int c = C > 0 ? C : c_rt;
+    int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= n_items) return;
+    int chunk = (int)(gid & 15);
+    int64_t tt = gid >> 4;
+    int64_t t = tt % tokens_out;
+    int64_t h = tt / tokens_out;
+    const bf16_t *src = x + h * stride_head + (t * c) * stride_tok + chunk * 8;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+    if (C > 0) {
+        u32x4 w[C > 0 ? C : 1];
+#pragma unroll
+        for (int m = 0; m < C; ++m) w[m] = *reinterpret_cast<const u32x4 *>(src + m * stride_tok);
+#pragma unroll
+        for (int m = 0; m < C; ++m) {
+            float f[8];
+            unpack8(w[m], f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = acc[e] + f[e];
+        }
+    } else {
+        for (int m = 0; m < c; ++m) {
+            u32x4 w = *reinterpret_cast<const u32x4 *>(src + m * stride_tok);
+            float f[8];
+            unpack8(w, f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = acc[e] + f[e];
+        }
+    }
+    const float cf = (float)c;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = acc[e] / cf;
+    *reinterpret_cast<u32x4 *>(out + (h * tokens_out + t) * kHeadDim + chunk * 8) = pack8_rne(acc);
+}
+
+hipError_t launch_avgpool_seq(const TensorView &x, int n_heads, int64_t total_tokens, int c, bf16_t *out,
+                              hipStream_t stream)
+{
+    int64_t tokens_out = total_tokens / c;
+    int64_t n_items = (int64_t)n_heads * tokens_out * 16;
+    if (n_items == 0) return hipSuccess;
+    dim3 grid((unsigned)((n_items + 255) / 256)), block(256);
+#define US_POOL(CC)                                                                                         \
+    hipLaunchKernelGGL(avgpool_seq_kernel<CC>, grid, block, 0, stream, x.ptr, x.stride_tok, x.stride_head, \
+                       tokens_out, c, n_items, out)
+    switch (c) {
+        case 4: US_POOL(4); break;
+        case 8: US_POOL(8); break;
+        case 16: US_POOL(16); break;
+        default: US_POOL(0); break;
+    }
+#undef US_POOL
+    return hipGetLastError();
+}
+
+// out[h'][t][:] = bf16(mean over m < c_h of x[h' c_h + m][t][:]); x, out contiguous [heads][tokens][128].
+__global__ __launch_bounds__(256) void avgpool_head_kernel(const bf16_t *__restrict__ x, int64_t tokens, int c_h,
+                                                           int64_t n_items, bf16_t *__restrict__ out)
+{
+    int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= n_items) return;
+    int chunk = (int)(gid & 15);
+    int64_t tt = gid >> 4;
+    int64_t t = tt % tokens;
+    int64_t hp = tt / tokens;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+    for (int m = 0; m < c_h; ++m) {
+        u32x4 w = *reinterpret_cast<const u32x4 *>(x + ((hp * c_h + m) * tokens + t) * kHeadDim + chunk * 8);
+        float f[8];
+        unpack8(w, f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = acc[e] + f[e];
+    }
+    const float cf = (float)c_h;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = acc[e] / cf;
+    *reinterpret_cast<u32x4 *>(out + (hp * tokens + t) * kHeadDim + chunk * 8) = pack8_rne(acc);
+}
+
+hipError_t launch_avgpool_head(const bf16_t *x, int n_heads_in, int64_t tokens, int c_h, bf16_t *out,
+                               hipStream_t stream)
+{
+    int64_t n_items = (int64_t)(n_heads_in / c_h) * tokens * 16;
+    if (n_items == 0) return hipSuccess;
+    dim3 grid((unsigned)((n_items + 255) / 256)), block(256);
+    hipLaunchKernelGGL(avgpool_head_kernel, grid, block, 0, stream, x, tokens, c_h, n_items, out);
+    return hipGetLastError();
+}
+
+}  // namespace us

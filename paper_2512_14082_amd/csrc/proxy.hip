@@ -1,0 +1,291 @@
+// Compressed-space scores, Alg. 1 steps 2-3: P~ = Q~ K~^T / sqrt(d_k), row softmax over composite
+// keys, block aggregation Score(i, j) of Eq. (3) with the index sets of Eq. (4).
+//
+// The (L/c_q) x (L/c_k) matrices P~ and A~ are never written to memory.  A workgroup of four
+// wavefronts owns 256 composite query rows that share one key head (4 query heads of a GQA group
+// x 64 rows, or fewer heads x more rows) and streams the composite keys through LDS in stages of
+// 128.  Each wavefront keeps its 64 query rows as MFMA B operands in registers and computes
+// 32-key x 64-query logit tiles transposed (S^T = K~ Q~^T, v_mfma_f32_32x32x16_bf16), so that every
+// lane owns whole query rows and the softmax statistics are lane-local.  Two sweeps over the
+// keys: the first finds each row's maximum and denominator, the second sums the normalised
+// probabilities over the composite keys of each key block (in registers), then over the
+// composite queries of each query block (cross-lane), and stores Score(i, j).
+#include "common.h"
+
+namespace us {
+
+constexpr int kPxThreads = 256;
+constexpr int kPxStageKeys = 128;          // composite keys per LDS stage
+constexpr int kPxPitch = 272;              // bytes per LDS row: 256 + 16 keeps 16-byte row reads conflict-free
+constexpr int kPxStageBytes = kPxStageKeys * kPxPitch;
+constexpr int kPxRowsPerWave = 64;
+
+struct ProxyGeom {
+    int HG;          // query heads of one key head handled by a workgroup (1, 2 or 4)
+    int RC;          // 64-row chunks per head in a workgroup (4 / HG)
+    int GS;          // head slices per key head (G / HG)
+    int n_tiles;     // query tiles over all sequences
+};
+
+template <int NQB, int NKB, bool CAUSAL>
+__global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeom g)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int lr = lane & 31;            // column of the MFMA tile this lane owns (a query row)
+    const int lh = lane >> 5;            // lane half
+
+    // ---- which (key head, head slice, sequence, query tile) ------------------------------------
+    const int vid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    const int per_kv = g.n_tiles * g.GS;
+    const int kvh = vid / per_kv;
+    int rem = vid % per_kv;
+    const int tile_rank = rem / g.GS;
+    const int gs = rem % g.GS;
+    int tile = g.n_tiles - 1 - tile_rank;                  // longest (latest) tiles first
+    const int rows_per_tile = kPxRowsPerWave * g.RC;
+    int seq = 0, qt = 0;
+    {
+        int base = 0;
+        for (int b = 0; b < a.st.num_seqs; ++b) {
+            int lq = (a.st.cu_tok[b + 1] - a.st.cu_tok[b]) / a.c_q;
+            int nt = (lq + rows_per_tile - 1) / rows_per_tile;
+            if (tile < base + nt) { seq = b; qt = tile - base; break; }
+            base += nt;
+        }
+    }
+    const int tok0 = a.st.cu_tok[seq];
+    const int Lb = a.st.cu_tok[seq + 1] - tok0;
+    const int Lq = Lb / a.c_q, Lk = Lb / a.c_k;
+    const int Nb = Lb / a.S;
+    const int64_t Tq = a.st.cu_tok[a.st.num_seqs] / a.c_q, Tk = a.st.cu_tok[a.st.num_seqs] / a.c_k;
+    int row_base = 0;                                       // packed query-block row of the sequence's block 0
+    for (int b = 0; b < seq; ++b) row_base += (a.st.cu_tok[b + 1] - a.st.cu_tok[b]) / a.S;
+
+    const int G = a.n_heads_q / a.n_heads_kv;
+    const int hh = wave % g.HG, rc = wave / g.HG;
+    const int head = kvh * G + gs * g.HG + hh;
+    const int t0 = (qt * g.RC + rc) * kPxRowsPerWave;       // first composite query row of this wavefront
+    const bool wave_active = t0 < Lq;
+
+    // highest visible composite key of a composite query row
+    auto limit_of = [&](int t) -> int {
+        int lim = Lk - 1;
+        if (CAUSAL) {
+            int c = ((t + 1) * a.c_q - 1) / a.c_k;
+            lim = c < lim ? c : lim;
+        }
+        return lim;
+    };
+    const int tile_last_row = min((qt + 1) * rows_per_tile, Lq) - 1;
+    const int n_stages = limit_of(tile_last_row) / kPxStageKeys + 1;
+    const int w_first = min(t0, Lq - 1), w_last = min(t0 + kPxRowsPerWave - 1, Lq - 1);
+    const int lim_first = limit_of(w_first), lim_last = limit_of(w_last);
+
+    // ---- query rows of this lane as B operands ---------------------------------------------------
+    bf16x8 qreg[2][8];
+    int lim_row[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        int t = min(t0 + 32 * qb + lr, Lq - 1);
+        lim_row[qb] = limit_of(t);
+        const bf16_t *src = a.qt + ((int64_t)head * Tq + tok0 / a.c_q + t) * kHeadDim + 8 * lh;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qreg[qb][ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
+    }
+
+    const bf16_t *kbase = a.kt + ((int64_t)kvh * Tk + tok0 / a.c_k) * kHeadDim;
+    u32x4 pre[8];
+    auto load_stage = [&](int st) {
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            int id = it * kPxThreads + tid;
+            int r = min(st * kPxStageKeys + (id >> 4), Lk - 1);
+            pre[it] = *reinterpret_cast<const u32x4 *>(kbase + (int64_t)r * kHeadDim + (id & 15) * 8);
+        }
+    };
+    auto store_stage = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            int id = it * kPxThreads + tid;
+            *reinterpret_cast<u32x4 *>(lds + buf * kPxStageBytes + (id >> 4) * kPxPitch + (id & 15) * 16) = pre[it];
+        }
+    };
+
+    const float c2 = a.scale_log2;
+    float m_run[2] = {-INFINITY, -INFINITY};
+    float l_run[2] = {0.0f, 0.0f};
+    float mc[2] = {0.0f, 0.0f}, wnorm[2] = {0.0f, 0.0f};
+
+#pragma unroll 1
+    for (int pass = 0; pass < 2; ++pass) {
+        load_stage(0);
+        __syncthreads();                                    // previous sweep finished reading LDS
+        store_stage(0);
+        __syncthreads();
+#pragma unroll 1
+        for (int st = 0; st < n_stages; ++st) {
+            const bool more = st + 1 < n_stages;
+            if (more) load_stage(st + 1);
+            const unsigned char *kb = lds + (st & 1) * kPxStageBytes;
+            if (wave_active) {
+#pragma unroll 1
+                for (int sub = 0; sub < 4; ++sub) {
+                    const int s_lo = st * kPxStageKeys + 32 * sub;
+                    if (s_lo > lim_last) break;
+                    const bool partial = s_lo + 31 > lim_first;
+                    f32x16 sacc[2];
+#pragma unroll
+                    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) sacc[qb][v] = 0.0f;
+                    const unsigned char *arow = kb + (32 * sub + lr) * kPxPitch + 16 * lh;
+#pragma unroll
+                    for (int ks = 0; ks < 8; ++ks) {
+                        bf16x8 ka = *reinterpret_cast<const bf16x8 *>(arow + 32 * ks);
+                        sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[0][ks], sacc[0], 0, 0, 0);
+                        sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[1][ks], sacc[1], 0, 0, 0);
+                    }
+                    if (partial) {
+#pragma unroll
+                        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) {
+                                int key = s_lo + 8 * (v >> 2) + 4 * lh + (v & 3);
+                                sacc[qb][v] = key <= lim_row[qb] ? sacc[qb][v] : -INFINITY;
+                            }
+                    }
+                    if (pass == 0) {
+#pragma unroll
+                        for (int qb = 0; qb < 2; ++qb) {
+                            float mx = sacc[qb][0];
+#pragma unroll
+                            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sacc[qb][v]);
+                            float m_new = fmaxf(m_run[qb], mx);
+                            float m_safe = m_new == -INFINITY ? 0.0f : m_new;
+                            float alpha = fast_exp2((m_run[qb] - m_safe) * c2);
+                            float msc = m_safe * c2;
+                            float sum = 0.0f;
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) sum += fast_exp2(fmaf(sacc[qb][v], c2, -msc));
+                            l_run[qb] = l_run[qb] * alpha + sum;
+                            m_run[qb] = m_new;
+                        }
+                    } else {
+                        constexpr int NBK = 32 / NKB;          // key blocks touched by a 32-key tile
+                        constexpr int GPB = NKB / 8;           // register groups (8 keys) per key block
+                        float bin[2][NBK];
+#pragma unroll
+                        for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+                            for (int b = 0; b < NBK; ++b) bin[qb][b] = 0.0f;
+#pragma unroll
+                            for (int v = 0; v < 16; ++v)
+                                bin[qb][(v >> 2) / GPB] += fast_exp2(fmaf(sacc[qb][v], c2, -mc[qb]));
+#pragma unroll
+                            for (int b = 0; b < NBK; ++b) {
+                                float x = bin[qb][b] * wnorm[qb];
+                                x += swap_half(x);
+#pragma unroll
+                                for (int off = 1; off < NQB; off <<= 1) x += __shfl_xor(x, off, 64);
+                                bin[qb][b] = x;
+                            }
+                        }
+                        if (lh == 0 && (lr % NQB) == 0) {
+#pragma unroll
+                            for (int qb = 0; qb < 2; ++qb) {
+                                int t = t0 + 32 * qb + lr;
+                                if (t < Lq) {
+                                    int i = t / NQB;
+                                    float *dst = a.score + ((int64_t)head * a.NQ + row_base + i) * a.NK;
+#pragma unroll
+                                    for (int b = 0; b < NBK; ++b) {
+                                        int j = s_lo / NKB + b;
+                                        if (j < Nb) dst[j] = bin[qb][b];
+                                    }
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+            if (more) store_stage((st + 1) & 1);
+            __syncthreads();
+        }
+        if (pass == 0) {
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                float m_o = swap_half(m_run[qb]), l_o = swap_half(l_run[qb]);
+                float m_t = fmaxf(m_run[qb], m_o);          // finite: every row sees at least key 0
+                float l_t = l_run[qb] * fast_exp2((m_run[qb] - m_t) * c2) + l_o * fast_exp2((m_o - m_t) * c2);
+                l_t = __shfl(l_t, lr, 64);                  // both halves use half 0's rounding of the sum
+                mc[qb] = m_t * c2;
+                wnorm[qb] = 1.0f / l_t;
+            }
+        }
+    }
+}
+
+static int proxy_pick_hg(int G)
+{
+    if (G % 4 == 0) return 4;
+    if (G % 2 == 0) return 2;
+    return 1;
+}
+
+template <int NQB, int NKB>
+static hipError_t proxy_launch_t(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream)
+{
+    const int lds_bytes = 2 * kPxStageBytes;
+    hipError_t e;
+    if (a.causal) {
+        static bool attr_done = false;
+        if (!attr_done) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&proxy_kernel<NQB, NKB, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL((proxy_kernel<NQB, NKB, true>), grid, dim3(kPxThreads), lds_bytes, stream, a, g);
+    } else {
+        static bool attr_done = false;
+        if (!attr_done) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&proxy_kernel<NQB, NKB, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL((proxy_kernel<NQB, NKB, false>), grid, dim3(kPxThreads), lds_bytes, stream, a, g);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_proxy_scores(const ProxyArgs &a, hipStream_t stream)
+{
+    ProxyGeom g;
+    const int G = a.n_heads_q / a.n_heads_kv;
+    g.HG = proxy_pick_hg(G);
+    g.RC = 4 / g.HG;
+    g.GS = G / g.HG;
+    const int rows_per_tile = kPxRowsPerWave * g.RC;
+    g.n_tiles = 0;
+    for (int b = 0; b < a.st.num_seqs; ++b) {
+        int lq = (a.st.cu_tok[b + 1] - a.st.cu_tok[b]) / a.c_q;
+        g.n_tiles += (lq + rows_per_tile - 1) / rows_per_tile;
+    }
+    int64_t nblk = (int64_t)a.n_heads_kv * g.GS * g.n_tiles;
+    if (nblk == 0) return hipSuccess;
+    dim3 grid((unsigned)nblk);
+    const int nq = a.S / a.c_q, nk = a.S / a.c_k;
+#define US_PX(NQB, NKB) \
+    if (nq == NQB && nk == NKB) return proxy_launch_t<NQB, NKB>(a, g, grid, stream)
+    US_PX(8, 8); US_PX(8, 16); US_PX(8, 32);
+    US_PX(16, 8); US_PX(16, 16); US_PX(16, 32);
+    US_PX(32, 8); US_PX(32, 16); US_PX(32, 32);
+#undef US_PX
+    return hipErrorInvalidValue;
+}
+
+}  // namespace us

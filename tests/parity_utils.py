@@ -1,0 +1,133 @@
+"""Shared machinery of the GPU parity tests: run the HIP path through the C ABI and compare with the oracle."""
+import numpy as np
+import torch
+
+from paper_2512_14082_amd import api
+from paper_2512_14082_amd import workloads as W
+
+MASK_AGREE_MIN = 0.999      # fraction of valid block decisions that must agree
+CUT_TOL = 1e-3              # a mismatch must lie within this of the cut (normalised score / cumulative share)
+OUT_MAX_ABS = 2e-2
+OUT_MEAN_ABS = 5e-3
+
+
+def device_tensors(w: W.Workload, layout="htd"):
+    q, k, v = (api.bits_to_device(x) for x in (w.q, w.k, w.v))
+    if layout == "thd":
+        q, k, v = (x.transpose(0, 1).contiguous() for x in (q, k, v))
+    return q, k, v
+
+
+def to_htd(x: torch.Tensor, layout):
+    return x if layout == "htd" else x.transpose(0, 1)
+
+
+def problem_of(w: W.Workload, scale=0.0):
+    return api.Problem(w.cu_seqlens, w.n_heads_q, w.n_heads_kv, w.block_size, w.causal, scale)
+
+
+def select_of(w: W.Workload):
+    return api.Select(w.c_q, w.c_k, w.c_h, w.mode, w.param if w.mode == W.TOP_P else 0.9,
+                      w.param if w.mode == W.TOP_K else 0.25)
+
+
+def row_geometry(cu, S):
+    loc, nb = [], []
+    for b in range(len(cu) - 1):
+        n = (cu[b + 1] - cu[b]) // S
+        loc += list(range(n))
+        nb += [n] * n
+    return np.array(loc), np.array(nb)
+
+
+def check_mask_against_oracle(m_gpu, m_ref, score_ref, cu, S, causal, mode, param, rows=None):
+    """>= 99.9 % of valid decisions equal; every mismatch admissible: the oracle's normalised score of the
+    block lies within 1e-3 of the row's cut, or (Top-P) the cumulative share next to it lies within 1e-3 of P."""
+    loc, nb = row_geometry(cu, S)
+    H, NQ, NK = m_ref.shape
+    c_h = H // score_ref.shape[0]
+    n_valid = n_bad = 0
+    rr = range(NQ) if rows is None else rows
+    for h in range(H):
+        for r in rr:
+            nv = loc[r] + 1 if causal else nb[r]
+            a, b = m_gpu[h, r, :nv], m_ref[h, r, :nv]
+            assert not m_gpu[h, r, nv:].any(), "bit outside the valid set"
+            assert a.any(), "empty mask row"
+            n_valid += nv
+            diff = np.nonzero(a != b)[0]
+            if len(diff) == 0:
+                continue
+            n_bad += len(diff)
+            sc = score_ref[h // c_h, r, :nv]
+            p = sc / sc.sum()
+            tau = p[b == 1].min()
+            order = np.lexsort((np.arange(nv), -p))
+            cum = np.cumsum(p[order])
+            pos = np.empty(nv, dtype=int)
+            pos[order] = np.arange(nv)
+            for j in diff:
+                ok = abs(p[j] - tau) <= CUT_TOL
+                if mode == W.TOP_P:
+                    before = cum[pos[j] - 1] if pos[j] > 0 else 0.0
+                    ok = ok or abs(before - param) <= CUT_TOL or abs(cum[pos[j]] - param) <= CUT_TOL
+                assert ok, f"inadmissible mask mismatch h={h} row={r} j={j} p={p[j]:.3e} tau={tau:.3e}"
+    agree = 1.0 - n_bad / max(1, n_valid)
+    assert agree >= MASK_AGREE_MIN, f"mask agreement {agree:.5f}"
+    return agree
+
+
+def check_output(o_gpu, o_ref, what=""):
+    sel = ~np.isnan(o_ref)
+    d = np.abs(o_gpu[sel].astype(np.float64) - o_ref[sel])
+    if not d.max() <= OUT_MAX_ABS:
+        full = np.where(sel, np.abs(o_gpu.astype(np.float64) - np.nan_to_num(o_ref)), 0.0)
+        bad_rows = np.argwhere(full.max(-1) > OUT_MAX_ABS)
+        raise AssertionError(f"{what} max-abs {d.max():.4f}; {len(bad_rows)} bad (head, token) rows of "
+                             f"{int(sel[..., 0].sum())}; first {bad_rows[:12].tolist()} last {bad_rows[-3:].tolist()}")
+    assert d.mean() <= OUT_MEAN_ABS, f"{what} mean-abs {d.mean():.5f}"
+    return d.max(), d.mean()
+
+
+def full_pipeline_check(ctx, oracle, w: W.Workload, layout="htd", check_dense=True, rows=None, score_rtol=2e-3):
+    """Pool, scores, mask, selection, sparse and dense attention of one workload against the oracle."""
+    q, k, v = device_tensors(w, layout)
+    qf, kf, vf = w.f32()
+    p, s = problem_of(w), select_of(w)
+    param = w.param
+    # -- pooling: bit exact
+    qt = ctx.avgpool_seq(q, w.c_q, layout)
+    torch.cuda.synchronize()
+    qt_bits = qt.view(torch.int16).cpu().numpy().view(np.uint16)
+    for h in range(w.n_heads_q):
+        ref = np.concatenate([oracle.avgpool_seq(qf[h, w.cu_seqlens[b]:w.cu_seqlens[b + 1]], w.c_q)
+                              for b in range(len(w.cu_seqlens) - 1)])
+        assert np.array_equal(qt_bits[h], W.f32_to_bf16_bits(ref)), f"pooling mismatch head {h}"
+    # -- scores and mask
+    m_dev, sc_dev = ctx.build_mask(p, s, q, k, layout, want_score=True)
+    torch.cuda.synchronize()
+    m_gpu = api.unpack_mask(m_dev, p.n_cols)
+    sc_gpu = sc_dev.cpu().numpy()
+    m_ref, sc_ref = oracle.build_mask(qf, kf, w.cu_seqlens, w.block_size, w.c_q, w.c_k, w.causal, w.mode, param,
+                                      c_h=w.c_h, rows=rows)
+    rr = slice(None) if rows is None else list(rows)
+    np.testing.assert_allclose(sc_gpu[:, rr], sc_ref[:, rr], rtol=score_rtol, atol=1e-6)
+    agree = check_mask_against_oracle(m_gpu, m_ref, sc_ref, w.cu_seqlens, w.block_size, w.causal, w.mode, param, rows)
+    # -- selection alone is index work: on the GPU's own scores it must match the oracle bit for bit
+    m_sel = oracle.select_mask(sc_gpu, w.cu_seqlens, w.block_size, w.causal, w.mode, param, rows)
+    m_sel = np.repeat(m_sel, w.c_h, axis=0)
+    assert np.array_equal(m_gpu[:, rr], m_sel[:, rr]), "selection differs from the oracle on identical scores"
+    # -- sparse attention on the GPU's own mask
+    o_dev, lse_dev = ctx.sparse_attn(p, q, k, v, m_dev, layout, want_lse=True)
+    torch.cuda.synchronize()
+    o_gpu = to_htd(o_dev, layout).float().cpu().numpy()
+    o_ref, lse_ref = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, w.block_size, w.causal, m_gpu, rows=rows)
+    check_output(o_gpu, o_ref, "sparse")
+    ls = ~np.isnan(lse_ref)
+    np.testing.assert_allclose(lse_dev.cpu().numpy()[ls], lse_ref[ls], rtol=1e-3, atol=2e-3)
+    if check_dense:
+        od_dev, _ = ctx.full_attn(p, q, k, v, layout)
+        torch.cuda.synchronize()
+        od_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, w.block_size, w.causal, None, rows=rows)
+        check_output(to_htd(od_dev, layout).float().cpu().numpy(), od_ref, "dense")
+    return agree

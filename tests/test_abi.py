@@ -1,0 +1,49 @@
+"""The C-ABI library loads and exports every entry point that include/unisparse.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+from paper_2512_14082_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in os.listdir(inc):
+        if fn.endswith(".h"):
+            text = open(os.path.join(inc, fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names.update(re.findall(r"\b(unisparse_[a-z_0-9]+)\s*\(", text))
+    return names
+
+
+def _library():
+    if not os.path.exists(api.LIB_PATH):
+        from paper_2512_14082_amd import build
+        build.build_library(verbose=False)
+    return ctypes.CDLL(api.LIB_PATH)
+
+
+def test_every_declared_symbol_is_exported():
+    lib = _library()
+    names = _declared()
+    assert len(names) >= 13
+    for n in names:
+        assert hasattr(lib, n), n
+    assert names == set(api.EXPORTS)
+
+
+def test_status_strings_and_size_queries_without_gpu():
+    lib = api.load_library()
+    assert lib.unisparse_status_string(0) == b"ok"
+    assert lib.unisparse_status_string(5) == b"workspace too small"
+    p = api.Problem([0, 1024, 1536], 8, 2, 128, True)
+    assert lib.unisparse_mask_row_words(p.c) == 1
+    assert lib.unisparse_mask_words(p.c) == 8 * 12 * 1
+    s = api.Select(c_h=2)
+    assert lib.unisparse_score_elems(p.c, s.c) == 4 * 12 * 8
+    assert lib.unisparse_workspace_bytes(p.c, s.c) > 0
+    bad = api.Problem([0, 100], 8, 2, 128, True)
+    assert lib.unisparse_mask_words(bad.c) == 0

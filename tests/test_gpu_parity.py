@@ -1,0 +1,155 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_14082_amd import api
+from paper_2512_14082_amd import workloads as W
+
+import parity_utils as PU
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    return api.Context(0)
+
+
+def test_config1_single_head(ctx, oracle):
+    """BASELINE config 1 in full: L = 2048, S = 64, top-25 % budget."""
+    w = W.single_head_planted()
+    agree = PU.full_pipeline_check(ctx, oracle, w)
+    print("cfg1 mask agreement", agree)
+
+
+@pytest.mark.parametrize("layout", ["htd", "thd"])
+@pytest.mark.parametrize("S,causal,mode,param", [
+    (128, True, W.TOP_P, 0.9),
+    (128, False, W.TOP_K, 0.3),
+    (64, True, W.TOP_K, 0.25),
+    (64, False, W.TOP_P, 0.8),
+])
+def test_small_gqa_varlen(ctx, oracle, layout, S, causal, mode, param):
+    """Several tiles, ragged sequence mix (1, 3 and 5 blocks), GQA 4:2 heads."""
+    w = W.random_small(H=4, Hkv=2, lengths=(S, 3 * S, 5 * S), S=S, causal=causal, mode=mode, param=param, seed=11)
+    PU.full_pipeline_check(ctx, oracle, w, layout)
+
+
+def test_planted_gqa_4k(ctx, oracle):
+    w = W.gqa_planted(L=4096, H=8, Hkv=2, S=128, P=0.95, seed=21)
+    PU.full_pipeline_check(ctx, oracle, w)
+
+
+@pytest.mark.parametrize("cq,ck", [(4, 4), (16, 16), (4, 16), (16, 4)])
+def test_other_granularities(ctx, oracle, cq, ck):
+    w = W.gqa_planted(L=2048, H=4, Hkv=2, S=128, P=0.9, seed=31)
+    w.c_q, w.c_k = cq, ck
+    PU.full_pipeline_check(ctx, oracle, w, check_dense=False)
+
+
+@pytest.mark.parametrize("c_h", [2, 4, 8])
+def test_head_compression(ctx, oracle, c_h):
+    """c_h inside a GQA group (2, 4) and spanning two key heads (8)."""
+    w = W.gqa_planted(L=1024, H=8, Hkv=2, S=128, P=0.9, seed=41)
+    w.c_h = c_h
+    PU.full_pipeline_check(ctx, oracle, w, check_dense=False)
+
+
+def test_full_mask_equals_dense_and_empty_rows(ctx, oracle):
+    w = W.random_small(H=2, Hkv=1, lengths=(512,), S=128, causal=True, seed=5)
+    q, k, v = PU.device_tensors(w)
+    p = PU.problem_of(w)
+    N = 4
+    full = np.tril(np.ones((2, N, N), np.uint8))
+    o_s, _ = ctx.sparse_attn(p, q, k, v, api.pack_mask(full))
+    o_d, _ = ctx.full_attn(p, q, k, v)
+    torch.cuda.synchronize()
+    assert torch.equal(o_s, o_d)                       # all blocks selected = dense, bit for bit
+    # garbage bits above the diagonal / beyond the sequence are ignored
+    noisy = np.ones((2, N, 64), np.uint8)
+    o_n, _ = ctx.sparse_attn(p, q, k, v, api.pack_mask(noisy))
+    torch.cuda.synchronize()
+    assert torch.equal(o_n, o_d)
+    # an empty row gives zeros and lse = -inf, other rows are untouched
+    hole = full.copy()
+    hole[0, 2, :] = 0
+    o_h, lse = ctx.sparse_attn(p, q, k, v, api.pack_mask(hole), want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.all(o_h[0, 256:384] == 0) and torch.all(torch.isinf(lse[0, 256:384]))
+    assert torch.equal(o_h[1], o_d[1]) and torch.equal(o_h[0, :256], o_d[0, :256])
+
+
+def test_rows_sum_to_one_and_determinism(ctx, oracle):
+    w = W.gqa_planted(L=2048, H=4, Hkv=2, S=128, P=0.9, seed=51)
+    q, k, v = PU.device_tensors(w)
+    p, s = PU.problem_of(w), PU.select_of(w)
+    m1, sc1 = ctx.build_mask(p, s, q, k, want_score=True)
+    m2, sc2 = ctx.build_mask(p, s, q, k, want_score=True)
+    ones = torch.ones_like(v)
+    o1, _ = ctx.sparse_attn(p, q, k, ones, m1)
+    o2, _ = ctx.sparse_attn(p, q, k, v, m1)
+    o3, _ = ctx.sparse_attn(p, q, k, v, m2)
+    torch.cuda.synchronize()
+    assert torch.equal(m1, m2) and torch.equal(sc1, sc2) and torch.equal(o2, o3)      # bit-reproducible
+    assert torch.allclose(o1.float(), torch.ones_like(o1, dtype=torch.float32), atol=8e-3)   # weights sum to 1
+    np.testing.assert_allclose(sc1.sum(-1).cpu().numpy(), 128 / 8, rtol=1e-4)     # score rows sum to S / c_q
+
+
+def test_softmax_scale_and_threshold_one(ctx, oracle):
+    w = W.random_small(H=2, Hkv=2, lengths=(384,), S=128, causal=True, mode=W.TOP_P, param=1.0, seed=9)
+    q, k, v = PU.device_tensors(w)
+    p, s = PU.problem_of(w, scale=0.05), PU.select_of(w)
+    m, _ = ctx.build_mask(p, s, q, k)
+    torch.cuda.synchronize()
+    assert np.array_equal(api.unpack_mask(m, 3), np.tril(np.ones((2, 3, 3), np.uint8)))   # P = 1 keeps all valid
+    o, _ = ctx.full_attn(p, q, k, v)
+    torch.cuda.synchronize()
+    qf, kf, vf = w.f32()
+    ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, 128, True, None, scale=0.05)
+    PU.check_output(o.float().cpu().numpy(), ref, "scaled dense")
+
+
+def test_error_paths(ctx):
+    w = W.random_small(H=2, Hkv=1, lengths=(256,), S=128)
+    q, k, v = PU.device_tensors(w)
+    bad = api.Problem([0, 200], 2, 1, 128, True)                 # length not a multiple of S
+    with pytest.raises(api.UnisparseError) as e:
+        ctx.full_attn(bad, q, k, v)
+    assert e.value.code == 2
+    p = PU.problem_of(w)
+    with pytest.raises(api.UnisparseError) as e:
+        ctx.build_mask(p, api.Select(c_q=3), q, k)
+    assert e.value.code == 2
+    with pytest.raises(api.UnisparseError) as e:
+        ctx.build_mask(p, api.Select(c_q=2), q, k)               # S / c = 64: no kernel
+    assert e.value.code == 4
+    with pytest.raises(api.UnisparseError) as e:
+        ctx.build_mask(p, api.Select(threshold=1.5), q, k)
+    assert e.value.code == 3
+    with pytest.raises(api.UnisparseError) as e:
+        ctx.build_mask(p, api.Select(), q, k, workspace=torch.empty(1024, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == 5
+
+
+def test_config2_shape_sampled_rows(ctx, oracle):
+    """Llama-3-8B-shaped layer at L = 32K: full GPU run, oracle on sampled query-block rows."""
+    w = W.gqa_planted()
+    rng = np.random.default_rng(1)
+    rows = sorted({0, 1, 255, *[int(x) for x in rng.integers(2, 255, 5)]})
+    q, k, v = PU.device_tensors(w)
+    qf, kf, vf = w.f32()
+    p, s = PU.problem_of(w), PU.select_of(w)
+    m_dev, sc_dev = ctx.build_mask(p, s, q, k, want_score=True)
+    torch.cuda.synchronize()
+    m_gpu = api.unpack_mask(m_dev, p.n_cols)
+    m_ref, sc_ref = oracle.build_mask(qf, kf, w.cu_seqlens, 128, 8, 8, True, w.mode, w.param, rows=rows)
+    np.testing.assert_allclose(sc_dev.cpu().numpy()[:, rows], sc_ref[:, rows], rtol=2e-3, atol=1e-6)
+    PU.check_mask_against_oracle(m_gpu, m_ref, sc_ref, w.cu_seqlens, 128, True, w.mode, w.param, rows)
+    density = m_gpu.sum() / (32 * 256 * 257 / 2)
+    print("cfg2 density", density)
+    o_dev, _ = ctx.sparse_attn(p, q, k, v, m_dev)
+    torch.cuda.synchronize()
+    heads = [0, 13, 31]
+    o_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, 128, True, m_gpu, rows=rows[:4], heads=heads)
+    PU.check_output(o_dev.float().cpu().numpy()[heads], o_ref[heads], "cfg2 sparse")
