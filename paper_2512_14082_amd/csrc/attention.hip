@@ -21,6 +21,8 @@
 // contiguously), with the 16-byte chunk index XOR-swizzled by the row so that the K operand reads
 // (32 rows, same column) and the V transpose reads (8 rows x 64 bytes) spread over all banks.  The
 // swizzle is applied by choosing which global chunk each lane fetches.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace us {
@@ -51,6 +53,7 @@ struct AttnOrder {
     int R;           // rows per chunk
     int n_rg;        // row groups = ceil(NQ / R)
     int n_chunks;    // n_rg * n_heads_kv
+    int head_major;  // 1: all row groups of key head 0, then head 1, ... ; 0: row groups outermost, heads rotated
 };
 
 template <int S, bool CAUSAL, bool DENSE>
@@ -73,11 +76,13 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     const int ci = (idx / cs) * kNumXcd + xcd;
     if (ci >= ord.n_chunks) return;
     const int slot = idx % cs;
-    const int rg = ci / a.n_heads_kv;
-    const int kvh = (ci % a.n_heads_kv + rg) % a.n_heads_kv;
-    const int row = a.NQ - 1 - (rg * ord.R + slot / G);
+    const int rg = ord.head_major ? ci % ord.n_rg : ci / a.n_heads_kv;
+    const int kvh = ord.head_major ? ci / ord.n_rg : (ci % a.n_heads_kv + rg) % a.n_heads_kv;
+    // consecutive workgroups of an XCD go to different shader engines: vary the row, not the head, fastest,
+    // so that no engine collects all workgroups of a dense (or sparse) head
+    const int row = a.NQ - 1 - (rg * ord.R + slot % ord.R);
     if (row < 0) return;
-    const int head = kvh * G + slot % G;
+    const int head = kvh * G + slot / ord.R;
     int seq, i, nb;
     locate_row(a.st, S, row, seq, i, nb);
     const int64_t tok0 = a.st.cu_tok[seq];
@@ -328,6 +333,10 @@ static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
     ord.R = G >= 32 ? 1 : 32 / G;
     ord.n_rg = (a.NQ + ord.R - 1) / ord.R;
     ord.n_chunks = ord.n_rg * a.n_heads_kv;
+    {
+        const char *e = getenv("UNISPARSE_ATTN_ORDER");
+        ord.head_major = e ? atoi(e) : 1;
+    }
     const int64_t per_xcd = (ord.n_chunks + kNumXcd - 1) / kNumXcd;
     const int64_t nblk = per_xcd * kNumXcd * ord.R * G;
     hipLaunchKernelGGL((attention_kernel<S, CAUSAL, DENSE>), dim3((unsigned)nblk), dim3(C::NT), C::kLdsBytes, stream,
