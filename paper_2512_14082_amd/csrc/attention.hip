@@ -128,25 +128,38 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     }
 
     // ---- direct-to-LDS block loads: lane l of a 1 KB load fills row l / 16, physical chunk l % 16 -----
+    // Issued as inline assembly so that the compiler does not serialise later LDS reads behind them; their
+    // completion is awaited explicitly (vmcnt) before the barrier that publishes the buffer.
     const bf16_t *kptr = a.k.ptr + (int64_t)kvh * a.k.stride_head + tok0 * a.k.stride_tok;
     const bf16_t *vptr = a.v.ptr + (int64_t)kvh * a.v.stride_head + tok0 * a.v.stride_tok;
     const int dma_row = lane >> 4, dma_chunk = lane & 15;
-    auto dma_tile = [&](int j, int buf) {
-        unsigned char *kb = lds + buf * C::kStageBytes;
-        unsigned char *vb = kb + C::kTileBytes;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+    auto dma16 = [](const void *gbase, uint32_t goff, uint32_t lds_addr) {
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
+                     :
+                     : "s"(gbase), "v"(goff), "s"(lds_addr)
+                     : "memory", "m0");
+    };
+    // per-lane byte offsets inside a block (row r, swizzled chunk); the block base is wave-uniform
+    uint32_t koff[C::kDma], voff[C::kDma];
 #pragma unroll
-        for (int it = 0; it < C::kDma; ++it) {
-            const int r = 4 * (it * C::NW + wave) + dma_row;       // row of the block
-            const int64_t grow = (int64_t)j * S + r;
-            const bf16_t *gk = kptr + grow * a.k.stride_tok + ((dma_chunk ^ k_swizzle(r)) * 8);
-            const bf16_t *gv = vptr + grow * a.v.stride_tok + ((dma_chunk ^ v_swizzle(r)) * 8);
-            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)gk,
-                                             (void __attribute__((address_space(3))) *)(kb + (it * C::NW + wave) * 1024),
-                                             16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)gv,
-                                             (void __attribute__((address_space(3))) *)(vb + (it * C::NW + wave) * 1024),
-                                             16, 0, 0);
-        }
+    for (int it = 0; it < C::kDma; ++it) {
+        const int r = 4 * (it * C::NW + wave) + dma_row;
+        koff[it] = (uint32_t)(r * a.k.stride_tok + (dma_chunk ^ k_swizzle(r)) * 8) * 2u;
+        voff[it] = (uint32_t)(r * a.v.stride_tok + (dma_chunk ^ v_swizzle(r)) * 8) * 2u;
+    }
+    // LDS map: K buffers at [0, 2 tiles), V buffers at [2 tiles, 4 tiles)
+    auto dma_k = [&](int j, int b) {
+        const bf16_t *base = kptr + (int64_t)j * S * a.k.stride_tok;
+#pragma unroll
+        for (int it = 0; it < C::kDma; ++it)
+            dma16(base, koff[it], lds_base + b * C::kTileBytes + (it * C::NW + wave) * 1024);
+    };
+    auto dma_v = [&](int j, int b) {
+        const bf16_t *base = vptr + (int64_t)j * S * a.v.stride_tok;
+#pragma unroll
+        for (int it = 0; it < C::kDma; ++it)
+            dma16(base, voff[it], lds_base + (2 + b) * C::kTileBytes + (it * C::NW + wave) * 1024);
     };
 
     f32x16 oacc[4];
@@ -157,118 +170,207 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     float m_run = -INFINITY, l_run = 0.0f;
     const float c2 = a.scale_log2;
     const int i16 = lane & 15;
-
-    int j = next_block();
-    if (j >= 0) dma_tile(j, 0);
-    __syncthreads();
-    int buf = 0;
-#pragma unroll 1
-    while (j >= 0) {
-        const int jn = next_block();
-        if (jn >= 0) dma_tile(jn, buf ^ 1);
-
-        const bool diag = CAUSAL && (j == i);
-        const bool wave_skip = diag && (C::KC * kh > 32 * qq + 31);
-        if (!wave_skip) {
-            const unsigned char *kb = lds + buf * C::kStageBytes;
-            const unsigned char *vb = kb + C::kTileBytes;
-            // ---- S^T = K Q^T ------------------------------------------------------------------------
-            f32x16 sacc[C::KB];
-            {
-                bf16x8 ka[C::KB][8];
+    f32x16 sacc[C::KB];
+    bf16x8 pb[C::KB][2];
 #pragma unroll
-                for (int t = 0; t < C::KB; ++t) {
-                    const int r = C::KC * kh + 32 * t + lr;
-                    const unsigned char *arow = kb + r * 256;
-                    const int sw = k_swizzle(r);
+    for (int t = 0; t < C::KB; ++t) {
 #pragma unroll
-                    for (int ks = 0; ks < 8; ++ks)
-                        ka[t][ks] = *reinterpret_cast<const bf16x8 *>(arow + (((2 * ks + lh) ^ sw) << 4));
-                }
+        for (int v = 0; v < 16; ++v) sacc[t][v] = 0.0f;
+    }
+
+    // ---- MFMA slot ----------------------------------------------------------------------------------------
+    // The slot is a flat chain of MFMA "units": first the PV product of the previous block (unit = one MFMA
+    // on 16 keys x 32 dims, operand = two transpose reads of V), then S^T of the current block (unit = one
+    // MFMA on 32 keys x 16 dims, operand = one 16-byte read of K).  Operand reads run kAhead units in front
+    // of the MFMA that consumes them, so LDS latency and issue time hide behind the matrix pipe; the
+    // scheduling barriers keep the compiler from collapsing the chain back into "all loads, then all MFMAs"
+    // (too many registers) or "load, wait, MFMA" (no overlap).
+    constexpr int NG = 2 * C::KB;                 // operand groups per block for K (4 k-steps) and V (16 keys)
+    constexpr int NU = 4 * NG;                    // MFMA units per product per block
+    constexpr int kAhead = 8;
+    bf16x8 opnd[kAhead];                          // operand ring
+    // Lane coordinates as the operand loads see them, passed through an empty asm at the start of every
+    // MFMA slot so that the swizzled LDS addresses are recomputed there instead of being kept alive as two
+    // dozen loop-invariant registers across the whole loop.
+    int lr_s = lr, lh_s = lh, i16_s = i16;
+    auto refresh_lane_ids = [&]() {
+        lr_s = lr; lh_s = lh; i16_s = i16;
+        asm volatile("" : "+v"(lr_s), "+v"(lh_s), "+v"(i16_s));
+    };
+    // PV unit u = (g, db): g = u / 4 = (t, half u2 of the 32-key tile), db = u % 4
+    auto v_fetch = [&](int bv, int u) -> bf16x8 {
+        const unsigned char *vb = lds + (2 + bv) * C::kTileBytes;
+        const int g = u >> 2, db = u & 3;
+        const int r0 = C::KC * kh + 16 * g + 4 * lh_s + (i16_s >> 2);            // + 8 for the second read
+        const int sw = v_swizzle(r0);                                            // same for row r0 + 8
+        const int chunk = (4 * db + 2 * (lr_s >> 4) + ((i16_s & 3) >> 1)) ^ sw;
+        const unsigned char *p0 = vb + r0 * 256 + (i16_s & 1) * 8 + (chunk << 4);
+        short4v x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(p0));
+        short4v x1 =
+            __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(p0 + 8 * 256));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // QK unit u = (t, ks): t = u / 8, ks = u % 8
+    auto k_fetch = [&](int bk, int u) -> bf16x8 {
+        const unsigned char *kb = lds + bk * C::kTileBytes;
+        const int t = u >> 3, ks = u & 7;
+        const int r = C::KC * kh + 32 * t + lr_s;
+        return *reinterpret_cast<const bf16x8 *>(kb + r * 256 + (((2 * ks + lh_s) ^ k_swizzle(r)) << 4));
+    };
+    auto m_slot = [&](int bk, int bv, bool has_pv, bool has_qk) {
+        const int n_pv = has_pv ? NU : 0, n_all = n_pv + (has_qk ? NU : 0);
+        auto fetch = [&](int w) {                 // w = position in the chain
+            if (w < n_pv) opnd[w % kAhead] = v_fetch(bv, w);
+            else opnd[w % kAhead] = k_fetch(bk, w - n_pv);
+        };
+#pragma unroll
+        for (int w = 0; w < kAhead; ++w)
+            if (w < n_all) fetch(w);
+#pragma unroll
+        for (int w = 0; w < 2 * NU; ++w) {
+            if (w < n_all) {
                 __builtin_amdgcn_sched_barrier(0);
+                const bf16x8 x = opnd[w % kAhead];
+                if (w < n_pv) {
+                    const int g = w >> 2, db = w & 3;
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, pb[g >> 1][g & 1], oacc[db], 0, 0, 0);
+                } else {
+                    const int u = w - n_pv, t = u >> 3, ks = u & 7;
+                    if (ks == 0) {
 #pragma unroll
-                for (int t = 0; t < C::KB; ++t)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) sacc[t][v] = 0.0f;
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-                    for (int t = 0; t < C::KB; ++t)
-                        sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t][ks], qreg[ks], sacc[t], 0, 0, 0);
-            }
-            if (diag) {
-#pragma unroll
-                for (int t = 0; t < C::KB; ++t)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        int key = C::KC * kh + 32 * t + 8 * (v >> 2) + 4 * lh + (v & 3);
-                        int qrow = 32 * qq + lr;
-                        sacc[t][v] = key <= qrow ? sacc[t][v] : -INFINITY;
+                        for (int v = 0; v < 16; ++v) sacc[t][v] = 0.0f;
                     }
-            }
-            // ---- online softmax, lane-local per query row -------------------------------------------
-            bf16x8 pb[C::KB][2];
-            {
-                float mx = -INFINITY;
-#pragma unroll
-                for (int t = 0; t < C::KB; ++t)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[t][v]);
-                mx = fmaxf(mx, swap_half(mx));
-                const float m_new = fmaxf(m_run, mx);
-                const float m_safe = m_new == -INFINITY ? 0.0f : m_new;
-                const float alpha = fast_exp2((m_run - m_safe) * c2);
-                const float msc = m_safe * c2;
-                float sum = 0.0f;
-#pragma unroll
-                for (int t = 0; t < C::KB; ++t) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        float p = fast_exp2(fmaf(sacc[t][v], c2, -msc));
-                        sum += p;
-                        sacc[t][v] = p;
-                    }
-#pragma unroll
-                    for (int u = 0; u < 2; ++u)
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) pb[t][u][e] = (bf16_t)sacc[t][8 * u + e];
+                    sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qreg[ks], sacc[t], 0, 0, 0);
                 }
-                l_run = l_run * alpha + sum;
-                m_run = m_new;
-                if (__any(alpha != 1.0f)) {
-#pragma unroll
-                    for (int db = 0; db < 4; ++db)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
-                }
-            }
-            // ---- O^T += V^T P^T ---------------------------------------------------------------------
-#pragma unroll
-            for (int t = 0; t < C::KB; ++t) {
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int r0 = C::KC * kh + 32 * t + 16 * u + 4 * lh + (i16 >> 2);   // + 8 for the second read
-                    const unsigned char *vrow = vb + r0 * 256 + (i16 & 1) * 8;
-                    const int sw = v_swizzle(r0);                                        // same for row r0 + 8
-#pragma unroll
-                    for (int db = 0; db < 4; ++db) {
-                        const int chunk = (4 * db + 2 * (lr >> 4) + ((i16 & 3) >> 1)) ^ sw;
-                        const unsigned char *p0 = vrow + (chunk << 4);
-                        short4v x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (short4v __attribute__((address_space(3))) *)(p0));
-                        short4v x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (short4v __attribute__((address_space(3))) *)(p0 + 8 * 256));
-                        const bf16x8 va =
-                            __builtin_bit_cast(bf16x8, __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7));
-                        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[t][u], oacc[db], 0, 0, 0);
-                    }
-                }
+                if (w + kAhead < n_all) fetch(w + kAhead);
             }
         }
-        __syncthreads();          // every wavefront is done with buf, and the loads into buf ^ 1 have landed
-        buf ^= 1;
-        j = jn;
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // ---- online softmax of the S^T tile, lane-local per query row; leaves P^T (bf16) in pb ---------------
+    auto softmax_phase = [&](bool diag) {
+        if (diag) {
+#pragma unroll
+            for (int t = 0; t < C::KB; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    int key = C::KC * kh + 32 * t + 8 * (v >> 2) + 4 * lh + (v & 3);
+                    int qrow = 32 * qq + lr;
+                    sacc[t][v] = key <= qrow ? sacc[t][v] : -INFINITY;
+                }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < C::KB; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[t][v]);
+        mx = fmaxf(mx, swap_half(mx));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_safe = m_new == -INFINITY ? 0.0f : m_new;
+        const float alpha = fast_exp2((m_run - m_safe) * c2);
+        const float msc = m_safe * c2;
+        float sum = 0.0f;
+#pragma unroll
+        for (int t = 0; t < C::KB; ++t) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float p = fast_exp2(fmaf(sacc[t][v], c2, -msc));
+                sum += p;
+                sacc[t][v] = p;
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pb[t][u][e] = (bf16_t)sacc[t][8 * u + e];
+        }
+        l_run = l_run * alpha + sum;
+        m_run = m_new;
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+        }
+        // P^T must be complete in this slot: without this the compiler sinks the exponentials past the
+        // barrier, next to the MFMAs that consume them, and the VALU work lands in the MFMA slot
+#pragma unroll
+        for (int t = 0; t < C::KB; ++t)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(pb[t][u]));
+        asm volatile("" : "+v"(l_run), "+v"(m_run));
+    };
+    // ---- software pipeline over the visited blocks ----------------------------------------------------------
+    // Per wavefront the work is a chain of slots  M_0 V_0 M_1 V_1 ... V_{N-1} M_N  separated by workgroup
+    // barriers, where M_n = { O^T += V P^T of block n-1 ; S^T of block n } (MFMA) and V_n = softmax of block
+    // n (VALU).  The two wavefronts of a SIMD (key halves kh = 0 / 1) run the same chain one slot apart, so
+    // one is in an MFMA slot while the other is in a VALU slot.  Block n's K must be in LDS by global slot
+    // 2n and its V by slot 2n + 2; both loads are issued at global slot 2n - 2 resp. 2n by every wavefront
+    // (which is the start of M_n for kh = 0 and the start of V_{n-1} for kh = 1) and awaited one slot later.
+    // Blocks are visited in ascending order, so only the last one can be the diagonal block.
+    auto wait_dma = []() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+    auto slot_barrier = []() {
+        __builtin_amdgcn_sched_barrier(0);     // keep each slot's instructions on their own side of the barrier
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int j_prev = -1, j_cur = next_block();
+    if (j_cur >= 0) {
+        int j_nxt = next_block();
+        dma_k(j_cur, 0);
+        wait_dma();
+        __syncthreads();
+        // global slot 0
+        if (j_nxt >= 0) dma_k(j_nxt, 1);
+        dma_v(j_cur, 0);
+        if (kh == 1) slot_barrier();                         // the late group idles through slot 0
+        __builtin_amdgcn_s_setprio(2);
+        refresh_lane_ids();
+        m_slot(0, 0, false, true);                           // M_0
+        __builtin_amdgcn_s_setprio(0);
+        if (kh == 1) wait_dma();
+        slot_barrier();
+        int n = 1;
+        j_prev = j_cur;
+        j_cur = j_nxt;
+#pragma unroll 1
+        while (j_cur >= 0) {
+            j_nxt = next_block();
+            // V_{n-1}
+            if (kh == 1) {
+                if (j_nxt >= 0) dma_k(j_nxt, (n + 1) & 1);
+                dma_v(j_cur, n & 1);
+            }
+            softmax_phase(false);
+            if (kh == 0) wait_dma();
+            slot_barrier();
+            refresh_lane_ids();
+            // M_n
+            if (kh == 0) {
+                if (j_nxt >= 0) dma_k(j_nxt, (n + 1) & 1);
+                dma_v(j_cur, n & 1);
+            }
+            __builtin_amdgcn_s_setprio(2);
+            m_slot(n & 1, (n - 1) & 1, true, true);
+            __builtin_amdgcn_s_setprio(0);
+            if (kh == 1) wait_dma();
+            slot_barrier();
+            j_prev = j_cur;
+            j_cur = j_nxt;
+            ++n;
+        }
+        // V_{N-1}: the last block may be the diagonal one
+        if (CAUSAL && j_prev == i) softmax_phase(true);
+        else softmax_phase(false);
+        if (kh == 0) wait_dma();
+        slot_barrier();
+        // M_N
+        refresh_lane_ids();
+        __builtin_amdgcn_s_setprio(2);
+        m_slot(0, (n - 1) & 1, true, false);
+        __builtin_amdgcn_s_setprio(0);
+        if (kh == 0) slot_barrier();                         // the early group idles through the last slot
     }
+    __syncthreads();
 
     // ---- merge the two key halves through LDS, normalise, store -------------------------------------
     l_run += swap_half(l_run);
