@@ -22,6 +22,7 @@
 // (32 rows, same column) and the V transpose reads (8 rows x 64 bytes) spread over all banks.  The
 // swizzle is applied by choosing which global chunk each lane fetches.
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.h"
 
@@ -61,7 +62,8 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
 {
     using C = AttnCfg<S>;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-    __shared__ uint64_t mwords[UNISPARSE_MAX_BLOCKS_PER_SEQ / 64];
+    __shared__ uint16_t jlist[UNISPARSE_MAX_BLOCKS_PER_SEQ];
+    __shared__ int jcount;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -88,34 +90,41 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     const int64_t tok0 = a.st.cu_tok[seq];
     const int nvalid = CAUSAL ? i + 1 : nb;
 
+    // The selected key blocks of this row, expanded once from the mask bits into an ascending list in LDS
+    // (one mask word per lane of wavefront 0, positions placed by a prefix sum of the popcounts).
+    int n_sel = nvalid;
     if (!DENSE) {
-        const int nw = (nvalid + 63) / 64;
-        for (int w = tid; w < nw; w += C::NT) {
-            uint64_t bits = a.mask[((int64_t)head * a.NQ + row) * a.W + w];
-            int hi = nvalid - w * 64;
-            if (hi < 64) bits &= (1ull << hi) - 1ull;
-            mwords[w] = bits;
+        if (wave == 0) {
+            const int nw = (nvalid + 63) / 64;
+            uint64_t bits = 0;
+            if (lane < nw) {
+                bits = a.mask[((int64_t)head * a.NQ + row) * a.W + lane];
+                const int hi = nvalid - lane * 64;
+                if (hi < 64) bits &= (1ull << hi) - 1ull;
+            }
+            const int cnt = __builtin_popcountll(bits);
+            int incl = cnt;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int up = __shfl_up(incl, off, 64);
+                if (lane >= off) incl += up;
+            }
+            int pos = incl - cnt;
+            while (bits != 0) {
+                jlist[pos++] = (uint16_t)(lane * 64 + __builtin_ctzll(bits));
+                bits &= bits - 1;
+            }
+            if (lane == 63) jcount = incl;
         }
         __syncthreads();
+        n_sel = __builtin_amdgcn_readfirstlane(jcount);
     }
-    int widx = -1;
-    uint64_t wbits = 0;
-    int jdense = 0;
-    auto next_block = [&]() -> int {
-        if (DENSE) {
-            int j = jdense < nvalid ? jdense : -1;
-            ++jdense;
-            return j;
-        } else {
-            const int nw = (nvalid + 63) / 64;
-            while (wbits == 0) {
-                if (++widx >= nw) return -1;
-                wbits = mwords[widx];
-            }
-            int j = widx * 64 + __builtin_ctzll(wbits);
-            wbits &= wbits - 1;
-            return __builtin_amdgcn_readfirstlane(j);
-        }
+    int cursor = 0;
+    auto next_block = [&]() __attribute__((always_inline)) -> int {
+        if (cursor >= n_sel) return -1;
+        const int j = DENSE ? cursor : __builtin_amdgcn_readfirstlane((int)jlist[cursor]);
+        ++cursor;
+        return j;
     };
 
     // ---- this wavefront's 32 query rows as B operands -------------------------------------------------
@@ -134,7 +143,7 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     const bf16_t *vptr = a.v.ptr + (int64_t)kvh * a.v.stride_head + tok0 * a.v.stride_tok;
     const int dma_row = lane >> 4, dma_chunk = lane & 15;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
-    auto dma16 = [](const void *gbase, uint32_t goff, uint32_t lds_addr) {
+    auto dma16 = [](const void *gbase, uint32_t goff, uint32_t lds_addr) __attribute__((always_inline)) {
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
                      :
                      : "s"(gbase), "v"(goff), "s"(lds_addr)
@@ -149,13 +158,13 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         voff[it] = (uint32_t)(r * a.v.stride_tok + (dma_chunk ^ v_swizzle(r)) * 8) * 2u;
     }
     // LDS map: K buffers at [0, 2 tiles), V buffers at [2 tiles, 4 tiles)
-    auto dma_k = [&](int j, int b) {
+    auto dma_k = [&](int j, int b) __attribute__((always_inline)) {
         const bf16_t *base = kptr + (int64_t)j * S * a.k.stride_tok;
 #pragma unroll
         for (int it = 0; it < C::kDma; ++it)
             dma16(base, koff[it], lds_base + b * C::kTileBytes + (it * C::NW + wave) * 1024);
     };
-    auto dma_v = [&](int j, int b) {
+    auto dma_v = [&](int j, int b) __attribute__((always_inline)) {
         const bf16_t *base = vptr + (int64_t)j * S * a.v.stride_tok;
 #pragma unroll
         for (int it = 0; it < C::kDma; ++it)
@@ -189,39 +198,53 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     constexpr int NU = 4 * NG;                    // MFMA units per product per block
     constexpr int kAhead = 8;
     bf16x8 opnd[kAhead];                          // operand ring
-    // Lane coordinates as the operand loads see them, passed through an empty asm at the start of every
-    // MFMA slot so that the swizzled LDS addresses are recomputed there instead of being kept alive as two
-    // dozen loop-invariant registers across the whole loop.
-    int lr_s = lr, lh_s = lh, i16_s = i16;
-    auto refresh_lane_ids = [&]() {
-        lr_s = lr; lh_s = lh; i16_s = i16;
-        asm volatile("" : "+v"(lr_s), "+v"(lh_s), "+v"(i16_s));
-    };
-    // PV unit u = (g, db): g = u / 4 = (t, half u2 of the 32-key tile), db = u % 4
-    auto v_fetch = [&](int bv, int u) -> bf16x8 {
-        const unsigned char *vb = lds + (2 + bv) * C::kTileBytes;
+    // Lane-constant LDS addresses of the operand reads, computed once; every read is "register + immediate".
+    typedef const unsigned char __attribute__((address_space(3))) * lds_ptr;
+    typedef short4v __attribute__((address_space(3))) * lds_s4_ptr;
+    typedef const bf16x8 __attribute__((address_space(3))) * lds_b8_ptr;
+    lds_ptr kaddr[8], vaddr[4];
+    {
+        lds_ptr lbase = (lds_ptr)lds;
+        const int r = C::KC * kh + lr;                                    // K row of tile t = 0 (t adds 32 rows)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) kaddr[ks] = lbase + (r * 256 + (((2 * ks + lh) ^ k_swizzle(r)) << 4));
+        const int r0 = C::KC * kh + 4 * lh + (i16 >> 2);                  // V row of group g = 0 (g adds 16 rows)
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            const int chunk = (4 * db + 2 * (lr >> 4) + ((i16 & 3) >> 1)) ^ v_swizzle(r0);
+            vaddr[db] = lbase + (2 * C::kTileBytes + r0 * 256 + (i16 & 1) * 8 + (chunk << 4));
+        }
+    }
+    // PV unit u = (g, db): g = u / 4 selects 16 keys, db = u % 4 selects 32 dims
+    auto v_fetch = [&](int u) __attribute__((always_inline)) -> bf16x8 {
         const int g = u >> 2, db = u & 3;
-        const int r0 = C::KC * kh + 16 * g + 4 * lh_s + (i16_s >> 2);            // + 8 for the second read
-        const int sw = v_swizzle(r0);                                            // same for row r0 + 8
-        const int chunk = (4 * db + 2 * (lr_s >> 4) + ((i16_s & 3) >> 1)) ^ sw;
-        const unsigned char *p0 = vb + r0 * 256 + (i16_s & 1) * 8 + (chunk << 4);
-        short4v x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(p0));
-        short4v x1 =
-            __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(p0 + 8 * 256));
+        lds_ptr p0 = vaddr[db] + 16 * g * 256;
+        short4v x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)p0);
+        short4v x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(p0 + 8 * 256));
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7));
     };
     // QK unit u = (t, ks): t = u / 8, ks = u % 8
-    auto k_fetch = [&](int bk, int u) -> bf16x8 {
-        const unsigned char *kb = lds + bk * C::kTileBytes;
+    auto k_fetch = [&](int u) __attribute__((always_inline)) -> bf16x8 {
         const int t = u >> 3, ks = u & 7;
-        const int r = C::KC * kh + 32 * t + lr_s;
-        return *reinterpret_cast<const bf16x8 *>(kb + r * 256 + (((2 * ks + lh_s) ^ k_swizzle(r)) << 4));
+        return *(lds_b8_ptr)(kaddr[ks] + 32 * t * 256);
     };
-    auto m_slot = [&](int bk, int bv, bool has_pv, bool has_qk) {
+    // kaddr / vaddr point into buffer 0 or 1; the other buffer is one block (a power of two) further or back
+    int k_flip = C::kTileBytes, v_flip = C::kTileBytes;
+    auto flip_k = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) kaddr[ks] += k_flip;
+        k_flip = -k_flip;
+    };
+    auto flip_v = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db) vaddr[db] += v_flip;
+        v_flip = -v_flip;
+    };
+    auto m_slot = [&](bool has_pv, bool has_qk) __attribute__((always_inline)) {
         const int n_pv = has_pv ? NU : 0, n_all = n_pv + (has_qk ? NU : 0);
-        auto fetch = [&](int w) {                 // w = position in the chain
-            if (w < n_pv) opnd[w % kAhead] = v_fetch(bv, w);
-            else opnd[w % kAhead] = k_fetch(bk, w - n_pv);
+        auto fetch = [&](int w) __attribute__((always_inline)) {                 // w = position in the chain
+            if (w < n_pv) opnd[w % kAhead] = v_fetch(w);
+            else opnd[w % kAhead] = k_fetch(w - n_pv);
         };
 #pragma unroll
         for (int w = 0; w < kAhead; ++w)
@@ -248,7 +271,7 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         __builtin_amdgcn_sched_barrier(0);
     };
     // ---- online softmax of the S^T tile, lane-local per query row; leaves P^T (bf16) in pb ---------------
-    auto softmax_phase = [&](bool diag) {
+    auto softmax_phase = [&](bool diag) __attribute__((always_inline)) {
         if (diag) {
 #pragma unroll
             for (int t = 0; t < C::KB; ++t)
@@ -307,8 +330,8 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     // 2n and its V by slot 2n + 2; both loads are issued at global slot 2n - 2 resp. 2n by every wavefront
     // (which is the start of M_n for kh = 0 and the start of V_{n-1} for kh = 1) and awaited one slot later.
     // Blocks are visited in ascending order, so only the last one can be the diagonal block.
-    auto wait_dma = []() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
-    auto slot_barrier = []() {
+    auto wait_dma = []() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+    auto slot_barrier = []() __attribute__((always_inline)) {
         __builtin_amdgcn_sched_barrier(0);     // keep each slot's instructions on their own side of the barrier
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
@@ -324,9 +347,9 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         dma_v(j_cur, 0);
         if (kh == 1) slot_barrier();                         // the late group idles through slot 0
         __builtin_amdgcn_s_setprio(2);
-        refresh_lane_ids();
-        m_slot(0, 0, false, true);                           // M_0
+        m_slot(false, true);                                 // M_0: K buffer 0
         __builtin_amdgcn_s_setprio(0);
+        flip_k();                                            // M_1 reads K buffer 1 and V buffer 0
         if (kh == 1) wait_dma();
         slot_barrier();
         int n = 1;
@@ -343,15 +366,16 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
             softmax_phase(false);
             if (kh == 0) wait_dma();
             slot_barrier();
-            refresh_lane_ids();
-            // M_n
+            // M_n: K buffer n & 1, V buffer (n - 1) & 1
             if (kh == 0) {
                 if (j_nxt >= 0) dma_k(j_nxt, (n + 1) & 1);
                 dma_v(j_cur, n & 1);
             }
             __builtin_amdgcn_s_setprio(2);
-            m_slot(n & 1, (n - 1) & 1, true, true);
+            m_slot(true, true);
             __builtin_amdgcn_s_setprio(0);
+            flip_k();
+            flip_v();
             if (kh == 1) wait_dma();
             slot_barrier();
             j_prev = j_cur;
@@ -363,10 +387,9 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         else softmax_phase(false);
         if (kh == 0) wait_dma();
         slot_barrier();
-        // M_N
-        refresh_lane_ids();
+        // M_N: PV product of block N-1
         __builtin_amdgcn_s_setprio(2);
-        m_slot(0, (n - 1) & 1, true, false);
+        m_slot(true, false);
         __builtin_amdgcn_s_setprio(0);
         if (kh == 0) slot_barrier();                         // the early group idles through the last slot
     }
