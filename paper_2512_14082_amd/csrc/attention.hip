@@ -149,26 +149,30 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
                      : "s"(gbase), "v"(goff), "s"(lds_addr)
                      : "memory", "m0");
     };
+    // Only the early group (kh = 0, wavefront index = qq) issues block loads, interleaved with its MFMA chain:
+    // kDmaA instructions of 1 KB (4 rows) per wavefront for K and as many for V.
+    constexpr int kDmaA = S / 4 / C::QW;
     // per-lane byte offsets inside a block (row r, swizzled chunk); the block base is wave-uniform
-    uint32_t koff[C::kDma], voff[C::kDma];
+    uint32_t koff[kDmaA], voff[kDmaA];
 #pragma unroll
-    for (int it = 0; it < C::kDma; ++it) {
-        const int r = 4 * (it * C::NW + wave) + dma_row;
+    for (int it = 0; it < kDmaA; ++it) {
+        const int r = 4 * (it * C::QW + qq) + dma_row;
         koff[it] = (uint32_t)(r * a.k.stride_tok + (dma_chunk ^ k_swizzle(r)) * 8) * 2u;
         voff[it] = (uint32_t)(r * a.v.stride_tok + (dma_chunk ^ v_swizzle(r)) * 8) * 2u;
     }
-    // LDS map: K buffers at [0, 2 tiles), V buffers at [2 tiles, 4 tiles)
-    auto dma_k = [&](int j, int b) __attribute__((always_inline)) {
-        const bf16_t *base = kptr + (int64_t)j * S * a.k.stride_tok;
-#pragma unroll
-        for (int it = 0; it < C::kDma; ++it)
-            dma16(base, koff[it], lds_base + b * C::kTileBytes + (it * C::NW + wave) * 1024);
-    };
-    auto dma_v = [&](int j, int b) __attribute__((always_inline)) {
-        const bf16_t *base = vptr + (int64_t)j * S * a.v.stride_tok;
-#pragma unroll
-        for (int it = 0; it < C::kDma; ++it)
-            dma16(base, voff[it], lds_base + (2 + b) * C::kTileBytes + (it * C::NW + wave) * 1024);
+    // LDS map: K buffers at [0, 2 tiles), V buffers at [2 tiles, 4 tiles).  Instruction d of a block pair:
+    // d < kDmaA loads K rows of block jk into K buffer bk, d >= kDmaA loads V rows of block jv into V buffer bv.
+    auto dma_one = [&](int d, int jk, int bk, int jv, int bv) __attribute__((always_inline)) {
+        if (d < kDmaA) {
+            if (jk >= 0)
+                dma16(kptr + (int64_t)jk * S * a.k.stride_tok, koff[d],
+                      lds_base + bk * C::kTileBytes + (d * C::QW + qq) * 1024);
+        } else {
+            const int e = d - kDmaA;
+            if (jv >= 0)
+                dma16(vptr + (int64_t)jv * S * a.v.stride_tok, voff[e],
+                      lds_base + (2 + bv) * C::kTileBytes + (e * C::QW + qq) * 1024);
+        }
     };
 
     f32x16 oacc[4];
@@ -240,15 +244,21 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         for (int db = 0; db < 4; ++db) vaddr[db] += v_flip;
         v_flip = -v_flip;
     };
-    auto m_slot = [&](bool has_pv, bool has_qk) __attribute__((always_inline)) {
+    // prefill: the first kAhead operand fetches of a chain (may be issued before the barrier that opens the slot
+    // when the data was published a slot earlier)
+    auto m_prefill = [&](bool has_pv, bool has_qk) __attribute__((always_inline)) {
         const int n_pv = has_pv ? NU : 0, n_all = n_pv + (has_qk ? NU : 0);
-        auto fetch = [&](int w) __attribute__((always_inline)) {                 // w = position in the chain
-            if (w < n_pv) opnd[w % kAhead] = v_fetch(w);
-            else opnd[w % kAhead] = k_fetch(w - n_pv);
-        };
 #pragma unroll
-        for (int w = 0; w < kAhead; ++w)
-            if (w < n_all) fetch(w);
+        for (int w = 0; w < kAhead; ++w) {
+            if (w < n_all) {
+                if (w < n_pv) opnd[w] = v_fetch(w);
+                else opnd[w] = k_fetch(w - n_pv);
+            }
+        }
+    };
+    // side(w) runs after the MFMA of unit w (used by the early group to issue block loads)
+    auto m_slot = [&](bool has_pv, bool has_qk, auto side) __attribute__((always_inline)) {
+        const int n_pv = has_pv ? NU : 0, n_all = n_pv + (has_qk ? NU : 0);
 #pragma unroll
         for (int w = 0; w < 2 * NU; ++w) {
             if (w < n_all) {
@@ -265,7 +275,12 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
                     }
                     sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qreg[ks], sacc[t], 0, 0, 0);
                 }
-                if (w + kAhead < n_all) fetch(w + kAhead);
+                if (w + kAhead < n_all) {
+                    const int w2 = w + kAhead;
+                    if (w2 < n_pv) opnd[w2 % kAhead] = v_fetch(w2);
+                    else opnd[w2 % kAhead] = k_fetch(w2 - n_pv);
+                }
+                side(w);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -339,18 +354,25 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     int j_prev = -1, j_cur = next_block();
     if (j_cur >= 0) {
         int j_nxt = next_block();
-        dma_k(j_cur, 0);
+        if (kh == 0) {
+#pragma unroll
+            for (int d = 0; d < kDmaA; ++d) dma_one(d, j_cur, 0, -1, 0);
+        }
         wait_dma();
         __syncthreads();
         // global slot 0
-        if (j_nxt >= 0) dma_k(j_nxt, 1);
-        dma_v(j_cur, 0);
         if (kh == 1) slot_barrier();                         // the late group idles through slot 0
+        m_prefill(false, true);
         __builtin_amdgcn_s_setprio(2);
-        m_slot(false, true);                                 // M_0: K buffer 0
+        // M_0 (K buffer 0); the early group loads K of block 1 and V of block 0 underneath, spread over the units
+        m_slot(false, true, [&](int w) __attribute__((always_inline)) {
+            if (kh == 0) {
+#pragma unroll
+                for (int d = w * 2 * kDmaA / NU; d < (w + 1) * 2 * kDmaA / NU; ++d) dma_one(d, j_nxt, 1, j_cur, 0);
+            }
+        });
         __builtin_amdgcn_s_setprio(0);
         flip_k();                                            // M_1 reads K buffer 1 and V buffer 0
-        if (kh == 1) wait_dma();
         slot_barrier();
         int n = 1;
         j_prev = j_cur;
@@ -358,25 +380,26 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll 1
         while (j_cur >= 0) {
             j_nxt = next_block();
-            // V_{n-1}
-            if (kh == 1) {
-                if (j_nxt >= 0) dma_k(j_nxt, (n + 1) & 1);
-                dma_v(j_cur, n & 1);
-            }
+            // V_{n-1}.  For the late group the blocks of its next MFMA slot were published a slot ago, so it
+            // puts that slot's first operand reads in flight before the barrier; the early group's blocks are
+            // published by this very barrier.
             softmax_phase(false);
+            if (kh == 1) m_prefill(true, true);
             if (kh == 0) wait_dma();
             slot_barrier();
-            // M_n: K buffer n & 1, V buffer (n - 1) & 1
-            if (kh == 0) {
-                if (j_nxt >= 0) dma_k(j_nxt, (n + 1) & 1);
-                dma_v(j_cur, n & 1);
-            }
+            // M_n: K buffer n & 1, V buffer (n - 1) & 1; loads of K block n+1 and V block n underneath
+            if (kh == 0) m_prefill(true, true);
             __builtin_amdgcn_s_setprio(2);
-            m_slot(true, true);
+            m_slot(true, true, [&](int w) __attribute__((always_inline)) {
+                if (kh == 0) {
+#pragma unroll
+                    for (int d = w * kDmaA / NU; d < (w + 1) * kDmaA / NU; ++d)
+                        dma_one(d, j_nxt, (n + 1) & 1, j_cur, n & 1);
+                }
+            });
             __builtin_amdgcn_s_setprio(0);
             flip_k();
             flip_v();
-            if (kh == 1) wait_dma();
             slot_barrier();
             j_prev = j_cur;
             j_cur = j_nxt;
@@ -385,11 +408,13 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         // V_{N-1}: the last block may be the diagonal one
         if (CAUSAL && j_prev == i) softmax_phase(true);
         else softmax_phase(false);
+        if (kh == 1) m_prefill(true, false);
         if (kh == 0) wait_dma();
         slot_barrier();
         // M_N: PV product of block N-1
+        if (kh == 0) m_prefill(true, false);
         __builtin_amdgcn_s_setprio(2);
-        m_slot(true, false);
+        m_slot(true, false, [](int) __attribute__((always_inline)) {});
         __builtin_amdgcn_s_setprio(0);
         if (kh == 0) slot_barrier();                         // the early group idles through the last slot
     }
