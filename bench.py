@@ -51,8 +51,8 @@ def cpu_baseline(w, m_gpu, valid_pairs_per_head, budget_s=20.0):
     H = w.n_heads_q
     NQ = m_gpu.shape[1]
     G = H // w.n_heads_kv
-    # proxy sample: every 16th query-block row of head 0
-    rows_p = list(range(NQ - 1, -1, -16))
+    # proxy sample: every 2nd query-block row of head 0
+    rows_p = list(range(NQ - 1, -1, -2))
     t0 = time.time()
     oracle.build_mask(qf[:1], kf[:1], w.cu_seqlens, w.block_size, w.c_q, w.c_k, w.causal, w.mode, w.param,
                       rows=rows_p)
@@ -65,7 +65,7 @@ def cpu_baseline(w, m_gpu, valid_pairs_per_head, budget_s=20.0):
     # attention sample: a few rows of head 0, scaled by selected block pairs
     pairs_total = float(m_gpu.sum())
     rows_a, t_attn, pairs_s = [], 0.0, 0.0
-    step = max(1, NQ // 8)
+    step = max(1, NQ // 64)
     for r in range(NQ - 1 - step // 2, -1, -step):
         t0 = time.time()
         oracle.masked_attention(qf, kf, vf, w.cu_seqlens, w.block_size, w.causal, m_gpu, rows=[r], heads=[0])
@@ -90,6 +90,8 @@ def main():
     ap.add_argument("--layout", default="htd", choices=["htd", "thd"])
     ap.add_argument("--dense-reps", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--profile-copy-mb", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X holds the whole layer); run with --gpus 1", file=sys.stderr)
@@ -122,6 +124,12 @@ def main():
         ctx.build_mask(p, s, q, k, lay, workspace=ws, mask=mask)
         ctx.sparse_attn(p, q, k, v, mask, lay, out=o)
 
+    if args.profile_copy_mb > 0:
+        src = torch.empty(args.profile_copy_mb << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -21,9 +21,6 @@
 // contiguously), with the 16-byte chunk index XOR-swizzled by the row so that the K operand reads
 // (32 rows, same column) and the V transpose reads (8 rows x 64 bytes) spread over all banks.  The
 // swizzle is applied by choosing which global chunk each lane fetches.
-#include <cstdlib>
-#include <type_traits>
-
 #include "common.h"
 
 namespace us {
@@ -46,14 +43,15 @@ __device__ __forceinline__ int k_swizzle(int row) { return row & 15; }
 __device__ __forceinline__ int v_swizzle(int row) { return (row & 3) << 2; }
 
 // Work order.  The hardware deals workgroup ids round-robin to the 8 XCDs (private L2 each), and each
-// XCD works through its share in order.  Workgroups are grouped in chunks of (one key head) x (R
-// consecutive query-block rows) x (its G query heads), about 32 workgroups that read the same K/V; chunk
-// number ci runs on XCD ci % 8, longest rows first, and the key head is rotated against the row group
-// so that every XCD sees every head (masks of different heads have different densities).
+// XCD works through its share in order.  Workgroups are grouped in chunks of (HG query heads of one key
+// head) x (R consecutive query-block rows), 32 workgroups that read the same K/V; chunk number ci runs on
+// XCD ci % 8, longest rows first, and the head group is rotated against the row group so that every XCD
+// sees every head (masks of different heads have different densities).
 struct AttnOrder {
     int R;           // rows per chunk
+    int HG;          // query heads (of one key head) per chunk
     int n_rg;        // row groups = ceil(NQ / R)
-    int n_chunks;    // n_rg * n_heads_kv
+    int n_chunks;    // n_rg * (n_heads_q / HG)
     int head_major;  // 1: all row groups of key head 0, then head 1, ... ; 0: row groups outermost, heads rotated
 };
 
@@ -73,18 +71,20 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
 
     // ---- which (head, query-block row) ---------------------------------------------------------------
     const int G = a.n_heads_q / a.n_heads_kv;
-    const int cs = ord.R * G;
+    const int cs = ord.R * ord.HG;
     const int xcd = blockIdx.x % kNumXcd, idx = blockIdx.x / kNumXcd;
     const int ci = (idx / cs) * kNumXcd + xcd;
     if (ci >= ord.n_chunks) return;
     const int slot = idx % cs;
-    const int rg = ord.head_major ? ci % ord.n_rg : ci / a.n_heads_kv;
-    const int kvh = ord.head_major ? ci / ord.n_rg : (ci % a.n_heads_kv + rg) % a.n_heads_kv;
+    const int n_hg = a.n_heads_q / ord.HG;                   // head groups
+    const int rg = ord.head_major ? ci % ord.n_rg : ci / n_hg;
+    const int hg = ord.head_major ? ci / ord.n_rg : (ci % n_hg + rg) % n_hg;
     // consecutive workgroups of an XCD go to different shader engines: vary the row, not the head, fastest,
     // so that no engine collects all workgroups of a dense (or sparse) head
     const int row = a.NQ - 1 - (rg * ord.R + slot % ord.R);
     if (row < 0) return;
-    const int head = kvh * G + slot / ord.R;
+    const int head = hg * ord.HG + slot / ord.R;
+    const int kvh = head / G;
     int seq, i, nb;
     locate_row(a.st, S, row, seq, i, nb);
     const int64_t tok0 = a.st.cu_tok[seq];
@@ -480,15 +480,13 @@ static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
     if (a.n_heads_q == 0 || a.NQ == 0) return hipSuccess;
     const int G = a.n_heads_q / a.n_heads_kv;
     AttnOrder ord;
-    ord.R = G >= 32 ? 1 : 32 / G;
+    ord.HG = G % 2 == 0 ? 2 : 1;
+    ord.R = 32 / ord.HG;
     ord.n_rg = (a.NQ + ord.R - 1) / ord.R;
-    ord.n_chunks = ord.n_rg * a.n_heads_kv;
-    {
-        const char *e = getenv("UNISPARSE_ATTN_ORDER");
-        ord.head_major = e ? atoi(e) : 1;
-    }
+    ord.n_chunks = ord.n_rg * (a.n_heads_q / ord.HG);
+    ord.head_major = 0;
     const int64_t per_xcd = (ord.n_chunks + kNumXcd - 1) / kNumXcd;
-    const int64_t nblk = per_xcd * kNumXcd * ord.R * G;
+    const int64_t nblk = per_xcd * kNumXcd * ord.R * ord.HG;
     hipLaunchKernelGGL((attention_kernel<S, CAUSAL, DENSE>), dim3((unsigned)nblk), dim3(C::NT), C::kLdsBytes, stream,
                        a, ord);
     return hipGetLastError();
