@@ -5,10 +5,15 @@
 // LDS (global_load_lds_dwordx4, no staging registers), double buffered: the next block's loads
 // are in flight during the current block's math and are awaited at the single barrier per block.
 //
-// Wavefront tiling (S = 128: eight wavefronts, two per SIMD so that one wavefront's softmax VALU
-// work overlaps the other's MFMAs): wavefront (qq, kh) owns query rows [32 qq, 32 qq + 32) and key
-// rows [64 kh, 64 kh + 64) of every visited block, with its own running max / sum / output; the
-// two key halves are merged through LDS once, after the last block.
+// Wavefront tiling: wavefront (qq, kh) owns query rows [32 qq, 32 qq + 32) and key rows [64 kh, 64 kh + 64)
+// of every visited block, with its own running max / sum / output; the key groups are merged through LDS
+// once, after the last block.  S = 128: eight wavefronts (two per SIMD); S = 64: two wavefronts.
+//
+// Every wavefront runs the same software pipeline over "sub-steps" of 32 keys: while the matrix pipe works
+// on S^T of sub-step s+1 and on the PV product of sub-step s-1, the VALU does the softmax of sub-step s, cut
+// into chunks of about four instructions that sit between consecutive MFMAs (an MFMA hides that much VALU
+// work of the same or the other wavefront of the SIMD; measured on gfx950, where dot-product and long runs
+// of transcendental instructions are the ones that do not hide).
 //
 // All matrix products are computed transposed so that a lane owns whole query rows:
 //   S^T (keys x queries)  = K Q^T   : A = K rows from LDS (16-byte reads), B = Q^T kept in registers
@@ -28,7 +33,7 @@ namespace us {
 template <int S>
 struct AttnCfg {
     static constexpr int QW = S / 32;            // query slices of 32 rows
-    static constexpr int KW = 2;                 // key halves
+    static constexpr int KW = S / 64;            // key groups of 64 rows
     static constexpr int NW = QW * KW;
     static constexpr int NT = NW * 64;
     static constexpr int KC = S / KW;            // keys per wavefront per block
@@ -149,29 +154,33 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
                      : "s"(gbase), "v"(goff), "s"(lds_addr)
                      : "memory", "m0");
     };
-    // Only the early group (kh = 0, wavefront index = qq) issues block loads, interleaved with its MFMA chain:
-    // kDmaA instructions of 1 KB (4 rows) per wavefront for K and as many for V.
-    constexpr int kDmaA = S / 4 / C::QW;
-    // per-lane byte offsets inside a block (row r, swizzled chunk); the block base is wave-uniform
-    uint32_t koff[kDmaA], voff[kDmaA];
+    // Every wavefront issues kDma instructions of 1 KB (4 rows) for K and as many for V per block.
+    constexpr int kDma = C::kDma;
+    // Per-lane byte offset of this lane's 16 bytes inside a block (row r, swizzled chunk) for the wavefront's
+    // first load; load number d of a block is 4 * NW rows further and that distance goes into the wave-uniform
+    // base address.  The K swizzle has a period of 16 rows: with 4 * NW = 8 the odd loads need an offset of
+    // their own (the V swizzle has a period of 4 rows).
+    constexpr int NKO = (4 * C::NW) % 16 == 0 ? 1 : 2;
+    uint32_t koff[NKO], voff0;
+    {
+        const int r = 4 * wave + dma_row;
 #pragma unroll
-    for (int it = 0; it < kDmaA; ++it) {
-        const int r = 4 * (it * C::QW + qq) + dma_row;
-        koff[it] = (uint32_t)(r * a.k.stride_tok + (dma_chunk ^ k_swizzle(r)) * 8) * 2u;
-        voff[it] = (uint32_t)(r * a.v.stride_tok + (dma_chunk ^ v_swizzle(r)) * 8) * 2u;
+        for (int o = 0; o < NKO; ++o)
+            koff[o] = (uint32_t)(r * a.k.stride_tok + (dma_chunk ^ k_swizzle(r + 4 * C::NW * o)) * 8) * 2u;
+        voff0 = (uint32_t)(r * a.v.stride_tok + (dma_chunk ^ v_swizzle(r)) * 8) * 2u;
     }
     // LDS map: K buffers at [0, 2 tiles), V buffers at [2 tiles, 4 tiles).  Instruction d of a block pair:
-    // d < kDmaA loads K rows of block jk into K buffer bk, d >= kDmaA loads V rows of block jv into V buffer bv.
+    // d < kDma loads K rows of block jk into K buffer bk, d >= kDma loads V rows of block jv into V buffer bv.
+    const int64_t k_step = (int64_t)4 * C::NW * a.k.stride_tok, v_step = (int64_t)4 * C::NW * a.v.stride_tok;
+    const uint32_t lds_wave = lds_base + wave * 1024;
     auto dma_one = [&](int d, int jk, int bk, int jv, int bv) __attribute__((always_inline)) {
-        if (d < kDmaA) {
-            if (jk >= 0)
-                dma16(kptr + (int64_t)jk * S * a.k.stride_tok, koff[d],
-                      lds_base + bk * C::kTileBytes + (d * C::QW + qq) * 1024);
+        if (d < kDma) {
+            dma16(kptr + (int64_t)jk * S * a.k.stride_tok + d * k_step, koff[d % NKO],
+                  lds_wave + bk * C::kTileBytes + d * C::NW * 1024);
         } else {
-            const int e = d - kDmaA;
-            if (jv >= 0)
-                dma16(vptr + (int64_t)jv * S * a.v.stride_tok, voff[e],
-                      lds_base + (2 + bv) * C::kTileBytes + (e * C::QW + qq) * 1024);
+            const int e = d - kDma;
+            dma16(vptr + (int64_t)jv * S * a.v.stride_tok + e * v_step, voff0,
+                  lds_wave + (2 + bv) * C::kTileBytes + e * C::NW * 1024);
         }
     };
 
@@ -183,24 +192,21 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     float m_run = -INFINITY, l_run = 0.0f;
     const float c2 = a.scale_log2;
     const int i16 = lane & 15;
-    f32x16 sacc[C::KB];
-    bf16x8 pb[C::KB][2];
-#pragma unroll
-    for (int t = 0; t < C::KB; ++t) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) sacc[t][v] = 0.0f;
-    }
+    static_assert(C::KB == 2, "the pipeline below works on two 32-key tiles per wavefront and block");
+    // The unit of the software pipeline is a "sub-step": one 32-key tile t of one block, numbered 2 n + t.
+    // State is kept twice, indexed by the parity of the sub-step (= t).
+    f32x16 sacc[2];                              // S^T tile
+    u32x4 pbw[2][2];                             // P^T tile as packed bf16 pairs: two MFMA operands of 16 keys
+    float sm_msc[2], sm_alpha[2], sm_sum[2];     // scaled running maximum, rescale factor, row sum of the tile
+    float sm_a[2][2], sm_x[2][2];                // exponent arguments / exponentials in flight (even, odd value)
+    float sm_ma = -INFINITY, sm_mb = -INFINITY;
 
-    // ---- MFMA slot ----------------------------------------------------------------------------------------
-    // The slot is a flat chain of MFMA "units": first the PV product of the previous block (unit = one MFMA
-    // on 16 keys x 32 dims, operand = two transpose reads of V), then S^T of the current block (unit = one
-    // MFMA on 32 keys x 16 dims, operand = one 16-byte read of K).  Operand reads run kAhead units in front
-    // of the MFMA that consumes them, so LDS latency and issue time hide behind the matrix pipe; the
-    // scheduling barriers keep the compiler from collapsing the chain back into "all loads, then all MFMAs"
-    // (too many registers) or "load, wait, MFMA" (no overlap).
-    constexpr int NG = 2 * C::KB;                 // operand groups per block for K (4 k-steps) and V (16 keys)
-    constexpr int NU = 4 * NG;                    // MFMA units per product per block
+    // ---- operand fetches -------------------------------------------------------------------------------
+    // MFMA "units": a QK unit is one MFMA on 32 keys x 16 dims (operand = one 16-byte read of K), a PV unit
+    // one MFMA on 16 keys x 32 dims (operand = two transpose reads of V).  Operand reads run kAhead units
+    // in front of the MFMA that consumes them.
     constexpr int kAhead = 8;
+    constexpr int kDmaGap = 2;                   // MFMA units between two block loads (when the chain is long enough)
     bf16x8 opnd[kAhead];                          // operand ring
     // Lane-constant LDS addresses of the operand reads, computed once; every read is "register + immediate".
     typedef const unsigned char __attribute__((address_space(3))) * lds_ptr;
@@ -219,20 +225,18 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
             vaddr[db] = lbase + (2 * C::kTileBytes + r0 * 256 + (i16 & 1) * 8 + (chunk << 4));
         }
     }
-    // PV unit u = (g, db): g = u / 4 selects 16 keys, db = u % 4 selects 32 dims
-    auto v_fetch = [&](int u) __attribute__((always_inline)) -> bf16x8 {
-        const int g = u >> 2, db = u & 3;
-        lds_ptr p0 = vaddr[db] + 16 * g * 256;
+    // PV operand: tile t, group g (16 keys) of the tile, dims block db
+    auto v_fetch = [&](int t, int g, int db) __attribute__((always_inline)) -> bf16x8 {
+        lds_ptr p0 = vaddr[db] + (32 * t + 16 * g) * 256;
         short4v x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)p0);
         short4v x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(p0 + 8 * 256));
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    // QK unit u = (t, ks): t = u / 8, ks = u % 8
-    auto k_fetch = [&](int u) __attribute__((always_inline)) -> bf16x8 {
-        const int t = u >> 3, ks = u & 7;
+    // QK operand: tile t, k-step ks
+    auto k_fetch = [&](int t, int ks) __attribute__((always_inline)) -> bf16x8 {
         return *(lds_b8_ptr)(kaddr[ks] + 32 * t * 256);
     };
-    // kaddr / vaddr point into buffer 0 or 1; the other buffer is one block (a power of two) further or back
+    // kaddr / vaddr point into buffer 0 or 1; the other buffer is one block further or back
     int k_flip = C::kTileBytes, v_flip = C::kTileBytes;
     auto flip_k = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -244,179 +248,223 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         for (int db = 0; db < 4; ++db) vaddr[db] += v_flip;
         v_flip = -v_flip;
     };
-    // prefill: the first kAhead operand fetches of a chain (may be issued before the barrier that opens the slot
-    // when the data was published a slot earlier)
-    auto m_prefill = [&](bool has_pv, bool has_qk) __attribute__((always_inline)) {
-        const int n_pv = has_pv ? NU : 0, n_all = n_pv + (has_qk ? NU : 0);
+
+    // ---- online softmax in chunks of a few instructions (lane-local per query row) -----------------------
+    // Per sub-step the 16 values of a lane go through
+    //   MX: row maximum, exchange with the other half of the key rows (lane ^ 32), running maximum, rescale
+    //       factor; also starts the pipeline below (arguments of values 0 and 1, exponential of value 0)
+    //   EX: one chunk per value u: [pack values u-1, u to bf16] row sum += exp(u); exp(u+1); argument(u+2)
+    //       - nothing in a chunk uses a result of the same chunk, so VALU latency never stalls the wavefront
+    // Every chunk is tied (empty asm) to the operand of the MFMA that follows it, which keeps it between the
+    // same two MFMAs in the machine code: the matrix pipe hides a handful of VALU instructions per MFMA.
+    auto sm_mask = [&](auto par_c) __attribute__((always_inline)) {          // diagonal block only
+        constexpr int par = decltype(par_c)::value;
 #pragma unroll
-        for (int w = 0; w < kAhead; ++w) {
-            if (w < n_all) {
-                if (w < n_pv) opnd[w] = v_fetch(w);
-                else opnd[w] = k_fetch(w - n_pv);
-            }
+        for (int v = 0; v < 16; ++v) {
+            int key = C::KC * kh + 32 * par + 8 * (v >> 2) + 4 * lh + (v & 3);
+            int qrow = 32 * qq + lr;
+            sacc[par][v] = key <= qrow ? sacc[par][v] : -INFINITY;
         }
     };
-    // side(w) runs after the MFMA of unit w (used by the early group to issue block loads)
-    auto m_slot = [&](bool has_pv, bool has_qk, auto side) __attribute__((always_inline)) {
-        const int n_pv = has_pv ? NU : 0, n_all = n_pv + (has_qk ? NU : 0);
-#pragma unroll
-        for (int w = 0; w < 2 * NU; ++w) {
-            if (w < n_all) {
-                __builtin_amdgcn_sched_barrier(0);
-                const bf16x8 x = opnd[w % kAhead];
-                if (w < n_pv) {
-                    const int g = w >> 2, db = w & 3;
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, pb[g >> 1][g & 1], oacc[db], 0, 0, 0);
-                } else {
-                    const int u = w - n_pv, t = u >> 3, ks = u & 7;
-                    if (ks == 0) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) sacc[t][v] = 0.0f;
-                    }
-                    sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qreg[ks], sacc[t], 0, 0, 0);
-                }
-                if (w + kAhead < n_all) {
-                    const int w2 = w + kAhead;
-                    if (w2 < n_pv) opnd[w2 % kAhead] = v_fetch(w2);
-                    else opnd[w2 % kAhead] = k_fetch(w2 - n_pv);
-                }
-                side(w);
-            }
+    constexpr int NMX = 6;
+    auto mx_chunk = [&](auto par_c, auto m_c, bf16x8 &next) __attribute__((always_inline)) {
+        constexpr int par = decltype(par_c)::value, m = decltype(m_c)::value;
+        const f32x16 &s = sacc[par];
+        if constexpr (m == 0) {
+            sm_ma = fmaxf(fmaxf(s[0], s[1]), s[2]);
+            sm_mb = fmaxf(fmaxf(s[3], s[4]), s[5]);
+            sm_ma = fmaxf(fmaxf(sm_ma, s[6]), s[7]);
+            asm volatile("" : "+v"(sm_ma), "+v"(sm_mb), "+v"(next));
+        } else if constexpr (m == 1) {
+            sm_mb = fmaxf(fmaxf(sm_mb, s[8]), s[9]);
+            sm_ma = fmaxf(fmaxf(sm_ma, s[10]), s[11]);
+            sm_mb = fmaxf(fmaxf(sm_mb, s[12]), s[13]);
+            sm_ma = fmaxf(fmaxf(sm_ma, s[14]), s[15]);
+            asm volatile("" : "+v"(sm_ma), "+v"(sm_mb), "+v"(next));
+        } else if constexpr (m == 2) {
+            const float mx = fmaxf(sm_ma, sm_mb);
+            auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+            sm_ma = fmaxf(fmaxf(m_run, __uint_as_float(sw[0])), __uint_as_float(sw[1]));     // new running maximum
+            asm volatile("" : "+v"(sm_ma), "+v"(next));
+        } else if constexpr (m == 3) {
+            const float m_safe = sm_ma == -INFINITY ? 0.0f : sm_ma;
+            sm_alpha[par] = fast_exp2((m_run - m_safe) * c2);
+            sm_msc[par] = m_safe * c2;
+            m_run = sm_ma;
+            asm volatile("" : "+v"(sm_alpha[par]), "+v"(sm_msc[par]), "+v"(m_run), "+v"(next));
+        } else if constexpr (m == 4) {
+            sm_a[par][0] = fmaf(s[0], c2, -sm_msc[par]);
+            sm_a[par][1] = fmaf(s[1], c2, -sm_msc[par]);
+            sm_sum[par] = 0.0f;
+            asm volatile("" : "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(sm_sum[par]), "+v"(next));
+        } else {
+            sm_x[par][0] = fast_exp2(sm_a[par][0]);
+            asm volatile("" : "+v"(sm_x[par][0]), "+v"(next));
         }
-        __builtin_amdgcn_sched_barrier(0);
     };
-    // ---- online softmax of the S^T tile, lane-local per query row; leaves P^T (bf16) in pb ---------------
-    auto softmax_phase = [&](bool diag) __attribute__((always_inline)) {
-        if (diag) {
-#pragma unroll
-            for (int t = 0; t < C::KB; ++t)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int key = C::KC * kh + 32 * t + 8 * (v >> 2) + 4 * lh + (v & 3);
-                    int qrow = 32 * qq + lr;
-                    sacc[t][v] = key <= qrow ? sacc[t][v] : -INFINITY;
-                }
+    auto ex_chunk = [&](auto par_c, auto u_c, bf16x8 &next) __attribute__((always_inline)) {
+        constexpr int par = decltype(par_c)::value, u = decltype(u_c)::value;
+        uint32_t w = 0;
+        if constexpr ((u & 1) != 0) {
+            f32x2 pe = {sm_x[par][0], sm_x[par][1]};
+            w = __builtin_bit_cast(uint32_t, __builtin_convertvector(pe, bf16x2));
         }
-        float mx = -INFINITY;
-#pragma unroll
-        for (int t = 0; t < C::KB; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[t][v]);
-        mx = fmaxf(mx, swap_half(mx));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_safe = m_new == -INFINITY ? 0.0f : m_new;
-        const float alpha = fast_exp2((m_run - m_safe) * c2);
-        const float msc = m_safe * c2;
-        float sum = 0.0f;
-#pragma unroll
-        for (int t = 0; t < C::KB; ++t) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float p = fast_exp2(fmaf(sacc[t][v], c2, -msc));
-                sum += p;
-                sacc[t][v] = p;
-            }
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pb[t][u][e] = (bf16_t)sacc[t][8 * u + e];
-        }
-        l_run = l_run * alpha + sum;
-        m_run = m_new;
-        if (__any(alpha != 1.0f)) {
+        sm_sum[par] += sm_x[par][u & 1];
+        if constexpr (u + 1 < 16) sm_x[par][(u + 1) & 1] = fast_exp2(sm_a[par][(u + 1) & 1]);
+        if constexpr (u + 2 < 16) sm_a[par][u & 1] = fmaf(sacc[par][u + 2], c2, -sm_msc[par]);
+        asm volatile("" : "+v"(w), "+v"(sm_sum[par]), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]), "+v"(sm_a[par][0]),
+                          "+v"(sm_a[par][1]), "+v"(next));
+        if constexpr ((u & 1) != 0) pbw[par][u >> 3][(u >> 1) & 3] = w;
+    };
+    // closes sub-step `par`: row sum, and O^T (which holds the products up to the sub-step before) rescaled
+    auto sm_finish = [&](auto par_c) __attribute__((always_inline)) {
+        constexpr int par = decltype(par_c)::value;
+        l_run = fmaf(l_run, sm_alpha[par], sm_sum[par]);
+        if (__any(sm_alpha[par] != 1.0f)) {
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+                for (int v = 0; v < 16; ++v) oacc[db][v] *= sm_alpha[par];
         }
-        // P^T must be complete in this slot: without this the compiler sinks the exponentials past the
-        // barrier, next to the MFMAs that consume them, and the VALU work lands in the MFMA slot
-#pragma unroll
-        for (int t = 0; t < C::KB; ++t)
-#pragma unroll
-            for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(pb[t][u]));
-        asm volatile("" : "+v"(l_run), "+v"(m_run));
     };
-    // ---- software pipeline over the visited blocks ----------------------------------------------------------
-    // Per wavefront the work is a chain of slots  M_0 V_0 M_1 V_1 ... V_{N-1} M_N  separated by workgroup
-    // barriers, where M_n = { O^T += V P^T of block n-1 ; S^T of block n } (MFMA) and V_n = softmax of block
-    // n (VALU).  The two wavefronts of a SIMD (key halves kh = 0 / 1) run the same chain one slot apart, so
-    // one is in an MFMA slot while the other is in a VALU slot.  Block n's K must be in LDS by global slot
-    // 2n and its V by slot 2n + 2; both loads are issued at global slot 2n - 2 resp. 2n by every wavefront
-    // (which is the start of M_n for kh = 0 and the start of V_{n-1} for kh = 1) and awaited one slot later.
-    // Blocks are visited in ascending order, so only the last one can be the diagonal block.
-    auto wait_dma = []() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
-    auto slot_barrier = []() __attribute__((always_inline)) {
-        __builtin_amdgcn_sched_barrier(0);     // keep each slot's instructions on their own side of the barrier
-        __builtin_amdgcn_s_barrier();
+    const std::integral_constant<int, 0> c0;
+    const std::integral_constant<int, 1> c1;
+
+    // ---- one iteration of the pipeline --------------------------------------------------------------------
+    // Iteration n (block n = j_n in the K/V buffers n & 1) is one chain of 32 MFMA units
+    //   [S^T of block n+1, tile 0] [PV of block n, tile 0] [S^T of block n+1, tile 1] [PV of block n, tile 1]
+    // with the softmax chunks of sub-steps 2n+1 (EX, units 0-15), 2n+2 (MX units 9-14, EX units 16-31) and 2n+3
+    // (MX units 25-30) between them: about four VALU instructions per MFMA everywhere.  The block loads of an
+    // iteration (K of block n+2 into the buffer of K block n, V of block n+1 into the buffer of V block n-1:
+    // both buffers were last read in the iteration before) are spread over the chain and awaited at the barrier
+    // that closes the iteration.  Without a block n+1 (has_qk = 0) the chain is the 16 PV units only.
+    auto iteration = [&](auto has_qk_c, auto diag_c, auto kload_c, auto vload_c, bool diag, int jk, int bk, int jv, int bv)
+                         __attribute__((always_inline)) {
+        constexpr bool has_qk = decltype(has_qk_c)::value != 0, may_diag = decltype(diag_c)::value != 0,
+                       kload = decltype(kload_c)::value != 0, vload = decltype(vload_c)::value != 0;
+        constexpr int n_all = has_qk ? 32 : 16;
+        auto fetch = [&](auto w_c) __attribute__((always_inline)) -> bf16x8 {
+            constexpr int w = decltype(w_c)::value;
+            constexpr int ph = has_qk ? (w >> 3) : 2 * (w >> 3) + 1, t = ph >> 1;
+            if constexpr ((ph & 1) == 0) return k_fetch(t, w & 7);
+            else return v_fetch(t, (w & 7) >> 2, w & 3);
+        };
+        static_for<kAhead>([&](auto w_c) __attribute__((always_inline)) { opnd[decltype(w_c)::value % kAhead] = fetch(w_c); });
+        static_for<n_all>([&](auto w_c) __attribute__((always_inline)) {
+            constexpr int w = decltype(w_c)::value;
+            constexpr int ph = has_qk ? (w >> 3) : 2 * (w >> 3) + 1, t = ph >> 1;
+            __builtin_amdgcn_sched_barrier(0);
+            const bf16x8 x = opnd[w % kAhead];
+            if constexpr ((ph & 1) == 0) {
+                constexpr int ks = w & 7;
+                f32x16 zero;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
+                sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qreg[ks], ks == 0 ? zero : sacc[t], 0, 0, 0);
+            } else {
+                constexpr int g = (w & 7) >> 2, db = w & 3;
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, __builtin_bit_cast(bf16x8, pbw[t][g]), oacc[db], 0, 0, 0);
+            }
+            if constexpr (w + kAhead < n_all) opnd[(w + kAhead) % kAhead] = fetch(std::integral_constant<int, (w + kAhead < n_all ? w + kAhead : 0)>{});
+            // block loads, evenly spread
+            constexpr int n_dma = (kload ? kDma : 0) + (vload ? kDma : 0);
+            if constexpr (n_dma > 0) {
+                constexpr int gap = kDmaGap * 2 * kDma <= n_all ? kDmaGap : n_all / (2 * kDma);
+                if constexpr (w % gap == gap / 2 && w / gap < 2 * kDma) {
+                    constexpr int d = w / gap;
+                    if constexpr (d < kDma) {
+                        if constexpr (kload) dma_one(d, jk, bk, jv, bv);
+                    } else {
+                        if constexpr (vload) dma_one(d, jk, bk, jv, bv);
+                    }
+                }
+            }
+            bf16x8 &next = opnd[(w + 1) % kAhead];
+            if constexpr (has_qk) {
+                if constexpr (w < 16) ex_chunk(c1, std::integral_constant<int, w % 16>{}, next);
+                else ex_chunk(c0, std::integral_constant<int, w % 16>{}, next);
+                if constexpr (may_diag && (w == 7 || w == 23)) {
+                    if (diag) sm_mask(std::integral_constant<int, (w == 23)>{});
+                }
+                if constexpr (w >= 9 && w < 9 + NMX) mx_chunk(c0, std::integral_constant<int, (w >= 9 && w < 9 + NMX ? w - 9 : 0)>{}, next);
+                if constexpr (w >= 25 && w < 25 + NMX) mx_chunk(c1, std::integral_constant<int, (w >= 25 && w < 25 + NMX ? w - 25 : 0)>{}, next);
+                if constexpr (w == 15) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    sm_finish(c1);
+                }
+                if constexpr (w == 31) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    sm_finish(c0);
+                }
+            } else {
+                if constexpr (w < 8) {
+                    ex_chunk(c1, std::integral_constant<int, (2 * w) % 16>{}, next);
+                    ex_chunk(c1, std::integral_constant<int, (2 * w + 1) % 16>{}, next);
+                }
+                if constexpr (w == 7) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    sm_finish(c1);
+                }
+            }
+        });
         __builtin_amdgcn_sched_barrier(0);
     };
-    int j_prev = -1, j_cur = next_block();
-    if (j_cur >= 0) {
-        int j_nxt = next_block();
-        if (kh == 0) {
+    auto wait_dma = []() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+    auto close_iteration = [&]() __attribute__((always_inline)) {
+        flip_k();
+        flip_v();
+        wait_dma();
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+    };
+
+    // ---- pipeline over the visited blocks (ascending, so only the last one can be the diagonal block) ------
+    const int j_first = next_block();
+    if (j_first >= 0) {
+        int j1 = next_block();                    // block n+1 at the top of iteration n
+        int j2 = j1 >= 0 ? next_block() : -1;     // block n+2
 #pragma unroll
-            for (int d = 0; d < kDmaA; ++d) dma_one(d, j_cur, 0, -1, 0);
+        for (int d = 0; d < 2 * kDma; ++d) dma_one(d, j_first, 0, j_first, 0);
+        if (j1 >= 0) {
+#pragma unroll
+            for (int d = 0; d < kDma; ++d) dma_one(d, j1, 1, -1, 0);
         }
         wait_dma();
         __syncthreads();
-        // global slot 0
-        if (kh == 1) slot_barrier();                         // the late group idles through slot 0
-        m_prefill(false, true);
-        __builtin_amdgcn_s_setprio(2);
-        // M_0 (K buffer 0); the early group loads K of block 1 and V of block 0 underneath, spread over the units
-        m_slot(false, true, [&](int w) __attribute__((always_inline)) {
-            if (kh == 0) {
+        // prologue: S^T of block 0, the whole softmax of its tile 0 and the maximum of its tile 1, unhidden
+        static_for<16>([&](auto w_c) __attribute__((always_inline)) {
+            constexpr int w = decltype(w_c)::value, t = w >> 3, ks = w & 7;
+            f32x16 zero;
 #pragma unroll
-                for (int d = w * 2 * kDmaA / NU; d < (w + 1) * 2 * kDmaA / NU; ++d) dma_one(d, j_nxt, 1, j_cur, 0);
-            }
+            for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
+            sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_fetch(t, ks), qreg[ks], ks == 0 ? zero : sacc[t], 0, 0, 0);
         });
-        __builtin_amdgcn_s_setprio(0);
-        flip_k();                                            // M_1 reads K buffer 1 and V buffer 0
-        slot_barrier();
-        int n = 1;
-        j_prev = j_cur;
-        j_cur = j_nxt;
-#pragma unroll 1
-        while (j_cur >= 0) {
-            j_nxt = next_block();
-            // V_{n-1}.  For the late group the blocks of its next MFMA slot were published a slot ago, so it
-            // puts that slot's first operand reads in flight before the barrier; the early group's blocks are
-            // published by this very barrier.
-            softmax_phase(false);
-            if (kh == 1) m_prefill(true, true);
-            if (kh == 0) wait_dma();
-            slot_barrier();
-            // M_n: K buffer n & 1, V buffer (n - 1) & 1; loads of K block n+1 and V block n underneath
-            if (kh == 0) m_prefill(true, true);
-            __builtin_amdgcn_s_setprio(2);
-            m_slot(true, true, [&](int w) __attribute__((always_inline)) {
-                if (kh == 0) {
-#pragma unroll
-                    for (int d = w * kDmaA / NU; d < (w + 1) * kDmaA / NU; ++d)
-                        dma_one(d, j_nxt, (n + 1) & 1, j_cur, n & 1);
-                }
-            });
-            __builtin_amdgcn_s_setprio(0);
-            flip_k();
-            flip_v();
-            slot_barrier();
-            j_prev = j_cur;
-            j_cur = j_nxt;
-            ++n;
+        if (CAUSAL && j1 < 0 && j_first == i) {
+            sm_mask(c0);
+            sm_mask(c1);
         }
-        // V_{N-1}: the last block may be the diagonal one
-        if (CAUSAL && j_prev == i) softmax_phase(true);
-        else softmax_phase(false);
-        if (kh == 1) m_prefill(true, false);
-        if (kh == 0) wait_dma();
-        slot_barrier();
-        // M_N: PV product of block N-1
-        if (kh == 0) m_prefill(true, false);
-        __builtin_amdgcn_s_setprio(2);
-        m_slot(true, false, [](int) __attribute__((always_inline)) {});
-        __builtin_amdgcn_s_setprio(0);
-        if (kh == 0) slot_barrier();                         // the early group idles through the last slot
+        static_for<NMX>([&](auto m_c) __attribute__((always_inline)) { mx_chunk(c0, m_c, opnd[0]); });
+        static_for<16>([&](auto u_c) __attribute__((always_inline)) { ex_chunk(c0, u_c, opnd[0]); });
+        l_run = sm_sum[0];
+        static_for<NMX>([&](auto m_c) __attribute__((always_inline)) { mx_chunk(c1, m_c, opnd[0]); });
+        flip_k();                                 // block 1's K is in buffer 1
+        __syncthreads();                          // K buffer 0 is reloaded from the first iteration on
+        int n = 0;
+        if (j1 >= 0) {
+#pragma unroll 1
+            while (j2 >= 0) {                     // block n+2 exists: every load of the iteration has a block to fetch
+                iteration(c1, c0, c1, c1, false, j2, n & 1, j1, (n + 1) & 1);
+                close_iteration();
+                j1 = j2;
+                j2 = next_block();
+                ++n;
+            }
+            // block n+1 is the last one: no K block to load; it may be the diagonal block
+            iteration(c1, c1, c0, c1, CAUSAL && j1 == i, -1, 0, j1, (n + 1) & 1);
+            close_iteration();
+        }
+        // the last block's P V
+        iteration(c0, c0, c0, c0, false, -1, 0, -1, 0);
     }
     __syncthreads();
 
@@ -434,7 +482,7 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     }
     __syncthreads();
     if (kh == 0) {
-        const float m1 = ml[lane], l1 = ml[64 + lane];
+        const float m1 = C::KW == 2 ? ml[lane] : -INFINITY, l1 = C::KW == 2 ? ml[64 + lane] : 0.0f;
         const float m0 = m_run, l0 = l_run;
         const float m_t = fmaxf(m0, m1);
         const bool empty = m_t == -INFINITY;
@@ -452,7 +500,7 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     int v = 4 * g + e;
-                    float o1 = mo[(db * 16 + v) * 64 + lane];
+                    float o1 = C::KW == 2 ? mo[(db * 16 + v) * 64 + lane] : 0.0f;
                     r[e] = (oacc[db][v] * a0 + o1 * a1) * inv;
                 }
                 u32x2 w;
