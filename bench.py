@@ -22,6 +22,21 @@ PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
+def _profiled_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel, as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
+    written down in profiles/ (a line `traffic_bytes_per_launch <workload> <bytes>`); None when there is no such line."""
+    path = os.path.join(ROOT, "profiles", "bench_cfg3_hbm_traffic.md")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == workload:
+                    return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
 def _events(n):
     import torch
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
@@ -176,7 +191,7 @@ def main():
         "pool_gbs": pool_bytes / (ms_pool * 1e-3) / 1e9,
         "roofline": {"kernel": "attention_kernel (block-sparse)", "bound": "mfma", "achieved": sparse_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": sparse_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": None},
+                     "traffic": _profiled_traffic(w.name)},
         "host_gen_s": t_gen,
     }
     if not args.no_cpu:
