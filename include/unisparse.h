@@ -84,7 +84,7 @@ typedef struct {
 
 /* Selection parameters (the inputs of Alg. 1 besides Q, K, V and S). */
 typedef struct {
-    int32_t c_q, c_k;                /* sequence compression factors; block_size / c must be 8, 16 or 32 */
+    int32_t c_q, c_k;                /* sequence compression factors; block_size / c must be 4, 8, 16, 32 or 64 */
     int32_t c_h;                     /* head compression factor; must divide H.  Groups of c_h query heads
                                         share one mask (Eq. (2) and the broadcast of Alg. 1) */
     int32_t mode;                    /* UNISPARSE_TOP_P or UNISPARSE_TOP_K */

@@ -65,7 +65,7 @@ unisparse_status check_select(const unisparse_problem *p, const unisparse_select
     if (s->c_q < 1 || s->c_k < 1 || s->c_h < 1) return UNISPARSE_ERR_PARAM;
     if (p->block_size % s->c_q != 0 || p->block_size % s->c_k != 0) return UNISPARSE_ERR_SHAPE;
     int nq = p->block_size / s->c_q, nk = p->block_size / s->c_k;
-    auto ok = [](int n) { return n == 8 || n == 16 || n == 32; };
+    auto ok = [](int n) { return n == 4 || n == 8 || n == 16 || n == 32 || n == 64; };
     if (!ok(nq) || !ok(nk)) return UNISPARSE_ERR_UNSUPPORTED;
     if (s->mode != UNISPARSE_TOP_P && s->mode != UNISPARSE_TOP_K) return UNISPARSE_ERR_PARAM;
     if (s->mode == UNISPARSE_TOP_P && !(s->threshold > 0.0 && s->threshold <= 1.0)) return UNISPARSE_ERR_PARAM;

@@ -174,8 +174,14 @@ __global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeo
                             m_run[qb] = m_new;
                         }
                     } else {
-                        constexpr int NBK = 32 / NKB;          // key blocks touched by a 32-key tile
-                        constexpr int GPB = NKB / 8;           // register groups (8 keys) per key block
+                        // Key blocks against the registers of a 32-key tile: register v of a lane holds key
+                        // 8 (v / 4) + 4 lh + v % 4.  n_k >= 8: a block is one or more groups of 8 keys, summed
+                        // over both lane halves; n_k = 4: a block is the four keys of one lane half; n_k = 64: a
+                        // block is two tiles, the second tile adds to what the first one stored.
+                        constexpr bool kHalfBlocks = NKB == 4, kTwoTiles = NKB == 64;
+                        constexpr int NBK = kHalfBlocks ? 4 : (NKB >= 32 ? 1 : 32 / NKB);   // bins per lane
+                        constexpr int GPB = kHalfBlocks ? 1 : (NKB >= 32 ? 4 : NKB / 8);    // register groups per bin
+                        constexpr int QR = NQB < 32 ? NQB : 32;                             // lanes of one query block
                         float bin[2][NBK];
 #pragma unroll
                         for (int qb = 0; qb < 2; ++qb) {
@@ -187,23 +193,30 @@ __global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeo
 #pragma unroll
                             for (int b = 0; b < NBK; ++b) {
                                 float x = bin[qb][b] * wnorm[qb];
-                                x += swap_half(x);
+                                if (!kHalfBlocks) x += swap_half(x);
 #pragma unroll
-                                for (int off = 1; off < NQB; off <<= 1) x += __shfl_xor(x, off, 64);
+                                for (int off = 1; off < QR; off <<= 1) x += __shfl_xor(x, off, 64);
                                 bin[qb][b] = x;
                             }
                         }
-                        if (lh == 0 && (lr % NQB) == 0) {
+                        if (NQB == 64) {                       // the wavefront's 64 rows are one query block
 #pragma unroll
-                            for (int qb = 0; qb < 2; ++qb) {
+                            for (int b = 0; b < NBK; ++b) bin[0][b] += bin[1][b];
+                        }
+                        if ((kHalfBlocks || lh == 0) && (lr % QR) == 0) {
+#pragma unroll
+                            for (int qb = 0; qb < (NQB == 64 ? 1 : 2); ++qb) {
                                 int t = t0 + 32 * qb + lr;
                                 if (t < Lq) {
                                     int i = t / NQB;
                                     float *dst = a.score + ((int64_t)head * a.NQ + row_base + i) * a.NK;
 #pragma unroll
                                     for (int b = 0; b < NBK; ++b) {
-                                        int j = s_lo / NKB + b;
-                                        if (j < Nb) dst[j] = bin[qb][b];
+                                        int j = kHalfBlocks ? s_lo / 4 + 2 * b + lh : s_lo / NKB + b;
+                                        if (j < Nb) {
+                                            if (kTwoTiles && (sub & 1)) dst[j] += bin[qb][b];
+                                            else dst[j] = bin[qb][b];
+                                        }
                                     }
                                 }
                             }
@@ -281,9 +294,11 @@ hipError_t launch_proxy_scores(const ProxyArgs &a, hipStream_t stream)
     const int nq = a.S / a.c_q, nk = a.S / a.c_k;
 #define US_PX(NQB, NKB) \
     if (nq == NQB && nk == NKB) return proxy_launch_t<NQB, NKB>(a, g, grid, stream)
-    US_PX(8, 8); US_PX(8, 16); US_PX(8, 32);
-    US_PX(16, 8); US_PX(16, 16); US_PX(16, 32);
-    US_PX(32, 8); US_PX(32, 16); US_PX(32, 32);
+    US_PX(4, 4); US_PX(4, 8); US_PX(4, 16); US_PX(4, 32); US_PX(4, 64);
+    US_PX(8, 4); US_PX(8, 8); US_PX(8, 16); US_PX(8, 32); US_PX(8, 64);
+    US_PX(16, 4); US_PX(16, 8); US_PX(16, 16); US_PX(16, 32); US_PX(16, 64);
+    US_PX(32, 4); US_PX(32, 8); US_PX(32, 16); US_PX(32, 32); US_PX(32, 64);
+    US_PX(64, 4); US_PX(64, 8); US_PX(64, 16); US_PX(64, 32); US_PX(64, 64);
 #undef US_PX
     return hipErrorInvalidValue;
 }

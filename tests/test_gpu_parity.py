@@ -41,7 +41,7 @@ def test_planted_gqa_4k(ctx, oracle):
     PU.full_pipeline_check(ctx, oracle, w)
 
 
-@pytest.mark.parametrize("cq,ck", [(4, 4), (16, 16), (4, 16), (16, 4)])
+@pytest.mark.parametrize("cq,ck", [(4, 4), (16, 16), (4, 16), (16, 4), (32, 2), (2, 32), (32, 32), (2, 2)])
 def test_other_granularities(ctx, oracle, cq, ck):
     w = W.gqa_planted(L=2048, H=4, Hkv=2, S=128, P=0.9, seed=31)
     w.c_q, w.c_k = cq, ck
@@ -122,7 +122,7 @@ def test_error_paths(ctx):
         ctx.build_mask(p, api.Select(c_q=3), q, k)
     assert e.value.code == 2
     with pytest.raises(api.UnisparseError) as e:
-        ctx.build_mask(p, api.Select(c_q=2), q, k)               # S / c = 64: no kernel
+        ctx.build_mask(p, api.Select(c_q=1), q, k)               # S / c = 128: no kernel
     assert e.value.code == 4
     with pytest.raises(api.UnisparseError) as e:
         ctx.build_mask(p, api.Select(threshold=1.5), q, k)
