@@ -11,8 +11,8 @@ to this code.
 Array conventions (host numpy, values exactly representable in bf16):
   Q : float32 [H, T, d]      K, V : float32 [H_kv, T, d]      T = sum of sequence lengths
   cu_seqlens : int sequence, B+1 entries, cu[0] = 0, cu[B] = T
-  mask  : uint8  [H, NQ, NK]  NQ = sum_b L_b / S (packed query-block rows),
-                              NK = max_b L_b / S; column j = key block j of the row's own sequence
+  mask  : uint8  [H, NQ, NK]  NQ = sum_b ceil(L_b / S) (packed query-block rows),
+                              NK = max_b ceil(L_b / S); column j = key block j of the row's own sequence
   score : float64 [H, NQ, NK] (0 outside the row's valid set)
 """
 from __future__ import annotations
@@ -120,9 +120,9 @@ def block_scores_head(qt: np.ndarray, kt: np.ndarray, S: int, c_q: int, c_k: int
     kt = _f32c(kt)
     Lq, d = qt.shape
     Lk = kt.shape[0]
-    N = (Lk * c_k) // S
+    N = -(-(Lk * c_k) // S)                      # the last block may be a shorter remainder
     if rows is None:
-        rows = np.arange((Lq * c_q) // S, dtype=np.int32)
+        rows = np.arange(-(-(Lq * c_q) // S), dtype=np.int32)
     rows = np.ascontiguousarray(rows, dtype=np.int32)
     out = np.zeros((len(rows), N), dtype=np.float64)
     lib.oracle_block_scores(_p(qt, ctypes.c_float), _p(kt, ctypes.c_float), Lq, Lk, d, S, c_q, c_k,
@@ -168,8 +168,7 @@ def _row_tables(cu_seqlens, S):
     seq_of, loc_of, nb_of = [], [], []
     for b in range(len(cu_seqlens) - 1):
         Lb = int(cu_seqlens[b + 1]) - int(cu_seqlens[b])
-        assert Lb % S == 0
-        nb = Lb // S
+        nb = -(-Lb // S)                         # ceil: a shorter last block when S does not divide L_b
         for i in range(nb):
             seq_of.append(b)
             loc_of.append(i)
@@ -216,7 +215,8 @@ def block_scores(Q: np.ndarray, K: np.ndarray, cu_seqlens: Sequence[int], S: int
     row0 = 0
     for b in range(len(cu_seqlens) - 1):
         t0, t1 = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
-        nb = (t1 - t0) // S
+        assert (t1 - t0) % c_q == 0 and (t1 - t0) % c_k == 0, "partial pooling windows are not defined here"
+        nb = -(-(t1 - t0) // S)
         loc = [i for i in range(nb) if (row0 + i) in want]
         if loc:
             for h in range(Hc):
@@ -267,7 +267,7 @@ def masked_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, cu_seqlens: Se
     for b in range(len(cu_seqlens) - 1):
         t0, t1 = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
         L = t1 - t0
-        nb = L // S
+        nb = -(-L // S)
         loc = np.array([i for i in range(nb) if (row0 + i) in want], dtype=np.int32)
         if len(loc):
             for h in hh:
@@ -285,8 +285,9 @@ def masked_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, cu_seqlens: Se
                                             _p(mb, ctypes.c_uint8), _p(loc, ctypes.c_int32), len(loc),
                                             _p(o, ctypes.c_double), _p(ls, ctypes.c_double))
                 for n, i in enumerate(loc):
-                    O[h, t0 + i * S:t0 + (i + 1) * S] = o[n]
-                    lse[h, t0 + i * S:t0 + (i + 1) * S] = ls[n]
+                    m = min(S, L - i * S)                    # tokens of the block that exist
+                    O[h, t0 + i * S:t0 + i * S + m] = o[n, :m]
+                    lse[h, t0 + i * S:t0 + i * S + m] = ls[n, :m]
         row0 += nb
     return O, lse
 

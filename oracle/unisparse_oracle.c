@@ -203,23 +203,30 @@ int oracle_select_top_k(const double *score, int n_valid, double f, uint8_t *sel
  * Block-masked attention of one head (Sec. 2.2):
  *   O = softmax(Q K^T * scale + M~) V,  M~ = 0 on selected blocks, -inf elsewhere,
  * plus token-level causality (s <= t) when causal != 0.
- *   q : [L][d];  k, v : [L][d];  mask : [N][N] bytes (N = L/S), row i = query block
+ *   q : [L][d];  k, v : [L][d];  mask : [N][N] bytes, N = ceil(L/S): when S does not divide L
+ *   the last block is the shorter remainder (the index sets of Eq. (4) clipped to the sequence)
  *   rows[n_rows] : query blocks to evaluate
  *   out : [n_rows][S][d],  lse : [n_rows][S] = log sum_s exp(logit)  (natural log)
- * A query with no visible key yields a zero row and lse = -inf.
+ * A query with no visible key yields a zero row and lse = -inf; so do the slots of the last
+ * block that lie beyond the sequence.
  */
 void oracle_masked_attention(const float *q, const float *k, const float *v, int64_t L, int d,
                              int S, int causal, double scale, const uint8_t *mask,
                              const int32_t *rows, int n_rows, double *out, double *lse)
 {
-    int64_t N = L / S;
+    int64_t N = (L + S - 1) / S;
     #pragma omp parallel for schedule(dynamic, 8)
     for (int64_t idx = 0; idx < (int64_t)n_rows * S; ++idx) {
         int r = (int)(idx / S);
         int64_t i = rows[r];
         int64_t t = i * S + idx % S;
-        const float *qrow = q + t * d;
         double *orow = out + idx * d;
+        if (t >= L) {                                   /* beyond the sequence: no query here */
+            for (int e = 0; e < d; ++e) orow[e] = 0.0;
+            lse[idx] = -INFINITY;
+            continue;
+        }
+        const float *qrow = q + t * d;
         double *p = (double *)malloc(sizeof(double) * (size_t)L);
         double pmax = -INFINITY;
         for (int64_t s = 0; s < L; ++s) {

@@ -397,3 +397,80 @@ def test_proxy_ranking_tracks_exact_block_mass(oracle):
     exact = oracle.block_scores(q, k, w.cu_seqlens, 128, 1, 1, True)[0] / 8.0
     rhos = [spearmanr(proxy[i, :i + 1], exact[i, :i + 1])[0] for i in range(8, 32)]
     assert np.mean(rhos) > 0.9
+
+
+# ----------------------------------------------------------------------------- ragged last block (S does not divide L)
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_ragged_scores_c1_equal_exact_block_mass(oracle, causal):
+    """L = 5 blocks and a remainder: with c = 1 the scores are the exact attention mass of the (clipped) blocks."""
+    rng = np.random.default_rng(50)
+    L, S, d = 88, 16, 32                                  # 5 full blocks + 8 tokens
+    q = bf16_values(rng, (L, d), 1.5)
+    k = bf16_values(rng, (L, d), 1.5)
+    sc = oracle.block_scores_head(q, k, S=S, c_q=1, c_k=1, causal_mode=int(causal), scale=1 / np.sqrt(d))
+    p = torch.from_numpy(q).double() @ torch.from_numpy(k).double().T / np.sqrt(d)
+    if causal:
+        p = p.masked_fill(torch.triu(torch.ones(L, L, dtype=torch.bool), 1), float("-inf"))
+    a = torch.softmax(p, -1)
+    N = -(-L // S)
+    pad = torch.zeros(N * S, N * S, dtype=torch.float64)
+    pad[:L, :L] = a
+    ref = pad.reshape(N, S, N, S).sum(dim=(1, 3)).numpy()
+    assert sc.shape == (N, N)
+    np.testing.assert_allclose(sc, ref, rtol=1e-10, atol=1e-13)
+
+
+def test_ragged_score_rows_sum_to_existing_composites(oracle):
+    rng = np.random.default_rng(51)
+    L, S, c = 200, 64, 8                                  # 3 full blocks + 8 tokens = one composite token
+    q = bf16_values(rng, (1, L, 32))
+    k = bf16_values(rng, (1, L, 32))
+    sc = oracle.block_scores(q, k, [0, L], S, c, c, causal=False)
+    np.testing.assert_allclose(sc[0].sum(-1), [8, 8, 8, 1], rtol=1e-12)
+    m, _ = oracle.build_mask(q, k, [0, L], S, c, c, True, 1, 0.5)
+    assert m.shape == (1, 4, 4) and not np.triu(m[0], 1).any() and m[0].any(-1).all()
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_ragged_masked_attention_matches_torch_sdpa(oracle, causal):
+    rng = np.random.default_rng(52)
+    L, d, S = 108, 32, 16                                 # 6 full blocks + 12 tokens
+    N = -(-L // S)
+    q, k, v = [bf16_values(rng, (1, L, d)) for _ in range(3)]
+    mask = (rng.random((1, N, N)) < 0.4).astype(np.uint8)
+    mask[0, np.arange(N), np.arange(N)] = 1
+    if causal:
+        mask = np.tril(mask)
+    O, lse = oracle.masked_attention(q, k, v, [0, L], S, causal, mask)
+    tq, tk, tv = [torch.from_numpy(x[0]).double() for x in (q, k, v)]
+    allowed = torch.from_numpy(np.kron(mask[0], np.ones((S, S), dtype=np.uint8))[:L, :L].copy()).bool()
+    if causal:
+        allowed &= torch.tril(torch.ones(L, L, dtype=torch.bool))
+    ro = torch.nn.functional.scaled_dot_product_attention(tq[None], tk[None], tv[None], attn_mask=allowed[None])[0]
+    rl = torch.logsumexp((tq @ tk.T / np.sqrt(d)).masked_fill(~allowed, float("-inf")), -1)
+    assert not np.isnan(O).any()
+    np.testing.assert_allclose(O[0], ro.numpy(), rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(lse[0], rl.numpy(), rtol=1e-9, atol=1e-12)
+
+
+def test_ragged_packed_sequences_are_independent(oracle):
+    rng = np.random.default_rng(53)
+    S, d = 16, 32
+    lens = [40, 16, 56]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    T = int(cu[-1])
+    q, k, v = [bf16_values(rng, (2, T, d)) for _ in range(3)]
+    m, sc = oracle.build_mask(q, k, cu, S, 8, 8, True, 0, 0.8)
+    assert m.shape[1] == 3 + 1 + 4
+    O, _ = oracle.masked_attention(q, k, v, cu, S, True, m)
+    assert not np.isnan(O).any()
+    r0 = 0
+    for b, Lb in enumerate(lens):
+        sl = slice(int(cu[b]), int(cu[b + 1]))
+        nb = -(-Lb // S)
+        mb, _ = oracle.build_mask(q[:, sl], k[:, sl], [0, Lb], S, 8, 8, True, 0, 0.8)
+        assert np.array_equal(mb, m[:, r0:r0 + nb, :nb])
+        Ob, _ = oracle.masked_attention(q[:, sl], k[:, sl], v[:, sl], [0, Lb], S, True, mb)
+        assert np.array_equal(Ob, O[:, sl])
+        r0 += nb
