@@ -19,10 +19,12 @@
  * - Element type of Q, K, V, O and of the composite tokens is bf16 (2 bytes).  head_dim = 128.
  * - A problem is a packed batch of B sequences ("varlen"): tokens of all sequences are
  *   concatenated along the token axis, sequence b owning tokens [cu_seqlens[b], cu_seqlens[b+1]).
- *   Every sequence length must be a multiple of block_size.  Sequences never interact.
+ *   Sequences never interact.  A length that is not a multiple of block_size gives a shorter last block
+ *   (the block index sets of Eq. (4) clipped to the sequence); build_mask additionally needs every length
+ *   to be a multiple of c_q and of c_k (whole pooling windows).
  * - Grouped-query attention: query head h uses key/value head h / (n_heads_q / n_heads_kv).
  * - Query-block rows are numbered over the packed batch: row r = (blocks of earlier sequences)
- *   + local block index i.  NQ = total_tokens / block_size rows, NK = max_b L_b / block_size.
+ *   + local block index i.  NQ = sum_b ceil(L_b / block_size) rows, NK = max_b ceil(L_b / block_size).
  * - Mask layout: uint64 M[n_heads_q][NQ][W], W = ceil(NK / 64).  Bit (j % 64) of word j / 64 of
  *   row r says whether query block r attends key block j *of its own sequence*.  Bits with
  *   j > i under causality and bits with j >= N_b are always written as 0 by build_mask and
@@ -51,7 +53,7 @@ typedef struct unisparse_ctx unisparse_ctx;   /* opaque; caches device propertie
 typedef enum {
     UNISPARSE_OK = 0,
     UNISPARSE_ERR_NULL = 1,          /* a required pointer is NULL */
-    UNISPARSE_ERR_SHAPE = 2,         /* lengths not multiples of block_size, c not dividing it, head counts ... */
+    UNISPARSE_ERR_SHAPE = 2,         /* lengths not multiples of c, c not dividing block_size, head counts ... */
     UNISPARSE_ERR_PARAM = 3,         /* threshold / budget outside (0, 1], unknown mode ... */
     UNISPARSE_ERR_UNSUPPORTED = 4,   /* valid request this build has no kernel for */
     UNISPARSE_ERR_WORKSPACE = 5,     /* workspace smaller than unisparse_workspace_bytes() */

@@ -123,12 +123,13 @@ class Problem:
 
     @property
     def n_rows(self) -> int:
-        return self.total_tokens // self.block_size
+        return sum(-(-(int(self.cu_seqlens[b + 1]) - int(self.cu_seqlens[b])) // self.block_size)
+                   for b in range(len(self.cu_seqlens) - 1))
 
     @property
     def n_cols(self) -> int:
-        return max(int(self.cu_seqlens[b + 1]) - int(self.cu_seqlens[b])
-                   for b in range(len(self.cu_seqlens) - 1)) // self.block_size
+        return -(-max(int(self.cu_seqlens[b + 1]) - int(self.cu_seqlens[b])
+                      for b in range(len(self.cu_seqlens) - 1)) // self.block_size)
 
 
 @dataclass

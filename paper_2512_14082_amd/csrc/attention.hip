@@ -93,6 +93,13 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     int seq, i, nb;
     locate_row(a.st, S, row, seq, i, nb);
     const int64_t tok0 = a.st.cu_tok[seq];
+    const int Lb = a.st.cu_tok[seq + 1] - a.st.cu_tok[seq];
+    // A sequence whose length is not a multiple of S ends in a shorter block: its missing rows are never
+    // loaded (row indices are clamped to the sequence), never attended (masked like the future keys of the
+    // diagonal block) and never stored.
+    const int j_short = Lb % S != 0 ? nb - 1 : -1;         // index of the shorter last block, if any
+    const int rows_short = Lb % S;                          // its number of rows
+    const int q_rows = i == j_short ? rows_short : S;       // query rows of this workgroup that exist
     const int nvalid = CAUSAL ? i + 1 : nb;
 
     // The selected key blocks of this row, expanded once from the mask bits into an ascending list in LDS
@@ -135,7 +142,8 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     // ---- this wavefront's 32 query rows as B operands -------------------------------------------------
     bf16x8 qreg[8];
     {
-        const bf16_t *src = a.q.ptr + (tok0 + (int64_t)i * S + 32 * qq + lr) * a.q.stride_tok +
+        const int qr = 32 * qq + lr < q_rows ? 32 * qq + lr : q_rows - 1;
+        const bf16_t *src = a.q.ptr + (tok0 + (int64_t)i * S + qr) * a.q.stride_tok +
                             (int64_t)head * a.q.stride_head + 8 * lh;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
@@ -182,6 +190,21 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
             dma16(vptr + (int64_t)jv * S * a.v.stride_tok + e * v_step, voff0,
                   lds_wave + (2 + bv) * C::kTileBytes + e * C::NW * 1024);
         }
+    };
+
+    // The same loads for a block that may be the shorter last one: rows beyond the sequence are replaced by its
+    // last row (only used outside the main loop, so the extra address arithmetic does not matter).
+    auto dma_clamped = [&](int d, int jk, int bk, int jv, int bv) __attribute__((always_inline)) {
+        const bool is_k = d < kDma;
+        const int e = is_k ? d : d - kDma, j = is_k ? jk : jv;
+        const int rows = j == j_short ? rows_short : S;
+        int r = 4 * (e * C::NW + wave) + dma_row;
+        const int swz = is_k ? k_swizzle(r) : v_swizzle(r);
+        r = r < rows ? r : rows - 1;
+        const int64_t st = is_k ? a.k.stride_tok : a.v.stride_tok;
+        const uint32_t off = (uint32_t)(r * st + (dma_chunk ^ swz) * 8) * 2u;
+        dma16((is_k ? kptr : vptr) + (int64_t)j * S * st, off,
+              lds_wave + (is_k ? bk : 2 + bv) * C::kTileBytes + e * C::NW * 1024);
     };
 
     f32x16 oacc[4];
@@ -257,15 +280,22 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     //       - nothing in a chunk uses a result of the same chunk, so VALU latency never stalls the wavefront
     // Every chunk is tied (empty asm) to the operand of the MFMA that follows it, which keeps it between the
     // same two MFMAs in the machine code: the matrix pipe hides a handful of VALU instructions per MFMA.
-    auto sm_mask = [&](auto par_c) __attribute__((always_inline)) {          // diagonal block only
+    // Last visited block only: keys after the query's own position (diagonal block of a causal row) and keys
+    // beyond the end of the sequence (shorter last block) are excluded.  key_max = highest admissible key row.
+    auto sm_mask = [&](auto par_c, int key_max) __attribute__((always_inline)) {
         constexpr int par = decltype(par_c)::value;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             int key = C::KC * kh + 32 * par + 8 * (v >> 2) + 4 * lh + (v & 3);
-            int qrow = 32 * qq + lr;
-            sacc[par][v] = key <= qrow ? sacc[par][v] : -INFINITY;
+            sacc[par][v] = key <= key_max ? sacc[par][v] : -INFINITY;
         }
     };
+    auto key_max_of = [&](int j) __attribute__((always_inline)) -> int {
+        int km = j == j_short ? rows_short - 1 : S - 1;
+        if (CAUSAL && j == i) km = min(km, 32 * qq + lr);
+        return km;
+    };
+    auto needs_mask = [&](int j) __attribute__((always_inline)) -> bool { return (CAUSAL && j == i) || j == j_short; };
     constexpr int NMX = 6;
     auto mx_chunk = [&](auto par_c, auto m_c, bf16x8 &next) __attribute__((always_inline)) {
         constexpr int par = decltype(par_c)::value, m = decltype(m_c)::value;
@@ -338,10 +368,12 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     // iteration (K of block n+2 into the buffer of K block n, V of block n+1 into the buffer of V block n-1:
     // both buffers were last read in the iteration before) are spread over the chain and awaited at the barrier
     // that closes the iteration.  Without a block n+1 (has_qk = 0) the chain is the 16 PV units only.
-    auto iteration = [&](auto has_qk_c, auto diag_c, auto kload_c, auto vload_c, bool diag, int jk, int bk, int jv, int bv)
+    auto iteration = [&](auto has_qk_c, auto diag_c, auto kload_c, auto vload_c, auto clamp_c, bool diag, int key_max, int jk, int bk,
+                         int jv, int bv)
                          __attribute__((always_inline)) {
         constexpr bool has_qk = decltype(has_qk_c)::value != 0, may_diag = decltype(diag_c)::value != 0,
-                       kload = decltype(kload_c)::value != 0, vload = decltype(vload_c)::value != 0;
+                       kload = decltype(kload_c)::value != 0, vload = decltype(vload_c)::value != 0,
+                       clamp = decltype(clamp_c)::value != 0;
         constexpr int n_all = has_qk ? 32 : 16;
         auto fetch = [&](auto w_c) __attribute__((always_inline)) -> bf16x8 {
             constexpr int w = decltype(w_c)::value;
@@ -372,10 +404,9 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
                 constexpr int gap = kDmaGap * 2 * kDma <= n_all ? kDmaGap : n_all / (2 * kDma);
                 if constexpr (w % gap == gap / 2 && w / gap < 2 * kDma) {
                     constexpr int d = w / gap;
-                    if constexpr (d < kDma) {
-                        if constexpr (kload) dma_one(d, jk, bk, jv, bv);
-                    } else {
-                        if constexpr (vload) dma_one(d, jk, bk, jv, bv);
+                    if constexpr ((d < kDma && kload) || (d >= kDma && vload)) {
+                        if constexpr (clamp) dma_clamped(d, jk, bk, jv, bv);
+                        else dma_one(d, jk, bk, jv, bv);
                     }
                 }
             }
@@ -384,7 +415,7 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
                 if constexpr (w < 16) ex_chunk(c1, std::integral_constant<int, w % 16>{}, next);
                 else ex_chunk(c0, std::integral_constant<int, w % 16>{}, next);
                 if constexpr (may_diag && (w == 7 || w == 23)) {
-                    if (diag) sm_mask(std::integral_constant<int, (w == 23)>{});
+                    if (diag) sm_mask(std::integral_constant<int, (w == 23)>{}, key_max);
                 }
                 if constexpr (w >= 9 && w < 9 + NMX) mx_chunk(c0, std::integral_constant<int, (w >= 9 && w < 9 + NMX ? w - 9 : 0)>{}, next);
                 if constexpr (w >= 25 && w < 25 + NMX) mx_chunk(c1, std::integral_constant<int, (w >= 25 && w < 25 + NMX ? w - 25 : 0)>{}, next);
@@ -424,10 +455,10 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         int j1 = next_block();                    // block n+1 at the top of iteration n
         int j2 = j1 >= 0 ? next_block() : -1;     // block n+2
 #pragma unroll
-        for (int d = 0; d < 2 * kDma; ++d) dma_one(d, j_first, 0, j_first, 0);
+        for (int d = 0; d < 2 * kDma; ++d) dma_clamped(d, j_first, 0, j_first, 0);
         if (j1 >= 0) {
 #pragma unroll
-            for (int d = 0; d < kDma; ++d) dma_one(d, j1, 1, -1, 0);
+            for (int d = 0; d < kDma; ++d) dma_clamped(d, j1, 1, -1, 0);
         }
         wait_dma();
         __syncthreads();
@@ -439,9 +470,10 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
             for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
             sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_fetch(t, ks), qreg[ks], ks == 0 ? zero : sacc[t], 0, 0, 0);
         });
-        if (CAUSAL && j1 < 0 && j_first == i) {
-            sm_mask(c0);
-            sm_mask(c1);
+        if (j1 < 0 && needs_mask(j_first)) {
+            const int km = key_max_of(j_first);
+            sm_mask(c0, km);
+            sm_mask(c1, km);
         }
         static_for<NMX>([&](auto m_c) __attribute__((always_inline)) { mx_chunk(c0, m_c, opnd[0]); });
         static_for<16>([&](auto u_c) __attribute__((always_inline)) { ex_chunk(c0, u_c, opnd[0]); });
@@ -452,19 +484,26 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         int n = 0;
         if (j1 >= 0) {
 #pragma unroll 1
-            while (j2 >= 0) {                     // block n+2 exists: every load of the iteration has a block to fetch
-                iteration(c1, c0, c1, c1, false, j2, n & 1, j1, (n + 1) & 1);
+            while (j2 >= 0 && j2 != j_short) {    // block n+2 exists and is a whole block: plain loads, no masking
+                iteration(c1, c0, c1, c1, c0, false, 0, j2, n & 1, j1, (n + 1) & 1);
                 close_iteration();
                 j1 = j2;
                 j2 = next_block();
                 ++n;
             }
-            // block n+1 is the last one: no K block to load; it may be the diagonal block
-            iteration(c1, c1, c0, c1, CAUSAL && j1 == i, -1, 0, j1, (n + 1) & 1);
+            if (j2 >= 0) {                        // block n+2 is the shorter last block of the sequence
+                iteration(c1, c0, c1, c1, c1, false, 0, j2, n & 1, j1, (n + 1) & 1);
+                close_iteration();
+                j1 = j2;
+                j2 = -1;
+                ++n;
+            }
+            // block n+1 is the last one: no K block to load; it may be the diagonal and / or the shorter block
+            iteration(c1, c1, c0, c1, c1, needs_mask(j1), key_max_of(j1), -1, 0, j1, (n + 1) & 1);
             close_iteration();
         }
         // the last block's P V
-        iteration(c0, c0, c0, c0, false, -1, 0, -1, 0);
+        iteration(c0, c0, c0, c0, c0, false, 0, -1, 0, -1, 0);
     }
     __syncthreads();
 
@@ -490,6 +529,7 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         const float a0 = fast_exp2((m0 - m_s) * c2), a1 = fast_exp2((m1 - m_s) * c2);
         const float l_t = l0 * a0 + l1 * a1;
         const float inv = empty ? 0.0f : 1.0f / l_t;
+        const bool row_exists = 32 * qq + lr < q_rows;
         const int64_t tok = tok0 + (int64_t)i * S + 32 * qq + lr;
         bf16_t *dst = a.o + tok * a.o_stride_tok + (int64_t)head * a.o_stride_head;
 #pragma unroll
@@ -506,10 +546,10 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
                 u32x2 w;
                 w[0] = f32_to_bf16_rne(r[0]) | (f32_to_bf16_rne(r[1]) << 16);
                 w[1] = f32_to_bf16_rne(r[2]) | (f32_to_bf16_rne(r[3]) << 16);
-                *reinterpret_cast<u32x2 *>(dst + 32 * db + 8 * g + 4 * lh) = w;
+                if (row_exists) *reinterpret_cast<u32x2 *>(dst + 32 * db + 8 * g + 4 * lh) = w;
             }
         }
-        if (a.lse != nullptr && lh == 0)
+        if (a.lse != nullptr && lh == 0 && row_exists)
             a.lse[(int64_t)head * a.total_tokens + tok] = empty ? -INFINITY : (__log2f(l_t) + m_t * c2) * kLn2;
     }
 }

@@ -38,10 +38,11 @@ unisparse_status check_problem(const unisparse_problem *p, Geom *g)
     int64_t nq = 0, nk = 0;
     for (int b = 0; b < p->num_seqs; ++b) {
         int64_t len = (int64_t)p->cu_seqlens[b + 1] - (int64_t)p->cu_seqlens[b];
-        if (len < 0 || len % p->block_size != 0) return UNISPARSE_ERR_SHAPE;
+        if (len < 0) return UNISPARSE_ERR_SHAPE;
+        const int64_t nb = (len + p->block_size - 1) / p->block_size;     // the last block may be a shorter remainder
         g->st.cu_tok[b] = p->cu_seqlens[b];
-        nq += len / p->block_size;
-        if (len / p->block_size > nk) nk = len / p->block_size;
+        nq += nb;
+        if (nb > nk) nk = nb;
     }
     g->st.cu_tok[p->num_seqs] = p->cu_seqlens[p->num_seqs];
     if (nk > UNISPARSE_MAX_BLOCKS_PER_SEQ) return UNISPARSE_ERR_UNSUPPORTED;
@@ -64,6 +65,10 @@ unisparse_status check_select(const unisparse_problem *p, const unisparse_select
     if (s == nullptr) return UNISPARSE_ERR_NULL;
     if (s->c_q < 1 || s->c_k < 1 || s->c_h < 1) return UNISPARSE_ERR_PARAM;
     if (p->block_size % s->c_q != 0 || p->block_size % s->c_k != 0) return UNISPARSE_ERR_SHAPE;
+    for (int b = 0; b < p->num_seqs; ++b) {           // whole pooling windows only
+        const int64_t len = (int64_t)p->cu_seqlens[b + 1] - (int64_t)p->cu_seqlens[b];
+        if (len % s->c_q != 0 || len % s->c_k != 0) return UNISPARSE_ERR_SHAPE;
+    }
     int nq = p->block_size / s->c_q, nk = p->block_size / s->c_k;
     auto ok = [](int n) { return n == 4 || n == 8 || n == 16 || n == 32 || n == 64; };
     if (!ok(nq) || !ok(nk)) return UNISPARSE_ERR_UNSUPPORTED;

@@ -39,14 +39,15 @@ struct TensorView {
     int64_t stride_head;
 };
 
-// Packed query-block row -> (sequence, local block index, blocks in that sequence).
+// Packed query-block row -> (sequence, local block index, blocks in that sequence).  A sequence whose length
+// is not a multiple of S ends in a shorter block.
 __device__ __forceinline__ void locate_row(const SeqTable &st, int S, int row, int &seq, int &local, int &nblk)
 {
     seq = 0;
     int base = 0;
 #pragma unroll 1
     for (int b = 0; b < st.num_seqs; ++b) {
-        int nb = (st.cu_tok[b + 1] - st.cu_tok[b]) / S;
+        int nb = (st.cu_tok[b + 1] - st.cu_tok[b] + S - 1) / S;
         if (row < base + nb) { seq = b; local = row - base; nblk = nb; return; }
         base += nb;
     }

@@ -59,10 +59,10 @@ __global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeo
     const int tok0 = a.st.cu_tok[seq];
     const int Lb = a.st.cu_tok[seq + 1] - tok0;
     const int Lq = Lb / a.c_q, Lk = Lb / a.c_k;
-    const int Nb = Lb / a.S;
+    const int Nb = (Lb + a.S - 1) / a.S;                    // the last block may be a shorter remainder
     const int64_t Tq = a.st.cu_tok[a.st.num_seqs] / a.c_q, Tk = a.st.cu_tok[a.st.num_seqs] / a.c_k;
     int row_base = 0;                                       // packed query-block row of the sequence's block 0
-    for (int b = 0; b < seq; ++b) row_base += (a.st.cu_tok[b + 1] - a.st.cu_tok[b]) / a.S;
+    for (int b = 0; b < seq; ++b) row_base += (a.st.cu_tok[b + 1] - a.st.cu_tok[b] + a.S - 1) / a.S;
 
     const int G = a.n_heads_q / a.n_heads_kv;
     const int hh = wave % g.HG, rc = wave / g.HG;
@@ -235,7 +235,8 @@ __global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeo
                 float l_t = l_run[qb] * fast_exp2((m_run[qb] - m_t) * c2) + l_o * fast_exp2((m_o - m_t) * c2);
                 l_t = __shfl(l_t, lr, 64);                  // both halves use half 0's rounding of the sum
                 mc[qb] = m_t * c2;
-                wnorm[qb] = 1.0f / l_t;
+                // rows beyond the sequence (clamped copies of its last row) must not count in a partial query block
+                wnorm[qb] = t0 + 32 * qb + lr < Lq ? 1.0f / l_t : 0.0f;
             }
         }
     }

@@ -80,7 +80,7 @@ class Workload:
         return self.q.shape[2]
 
     def n_blocks(self) -> List[int]:
-        return [(self.cu_seqlens[b + 1] - self.cu_seqlens[b]) // self.block_size
+        return [-(-(self.cu_seqlens[b + 1] - self.cu_seqlens[b]) // self.block_size)
                 for b in range(len(self.cu_seqlens) - 1)]
 
     def valid_pairs(self) -> int:

@@ -34,7 +34,7 @@ def select_of(w: W.Workload):
 def row_geometry(cu, S):
     loc, nb = [], []
     for b in range(len(cu) - 1):
-        n = (cu[b + 1] - cu[b]) // S
+        n = -(-(cu[b + 1] - cu[b]) // S)
         loc += list(range(n))
         nb += [n] * n
     return np.array(loc), np.array(nb)

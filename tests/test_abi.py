@@ -45,5 +45,7 @@ def test_status_strings_and_size_queries_without_gpu():
     s = api.Select(c_h=2)
     assert lib.unisparse_score_elems(p.c, s.c) == 4 * 12 * 8
     assert lib.unisparse_workspace_bytes(p.c, s.c) > 0
-    bad = api.Problem([0, 100], 8, 2, 128, True)
+    ragged = api.Problem([0, 100, 400], 8, 2, 128, True)          # 1 + 3 blocks, the last of each shorter
+    assert lib.unisparse_mask_words(ragged.c) == 8 * 4 * 1
+    bad = api.Problem([0, 100], 8, 3, 128, True)                  # heads do not divide
     assert lib.unisparse_mask_words(bad.c) == 0

@@ -36,6 +36,34 @@ def test_small_gqa_varlen(ctx, oracle, layout, S, causal, mode, param):
     PU.full_pipeline_check(ctx, oracle, w, layout)
 
 
+@pytest.mark.parametrize("S,causal,mode,param,layout", [
+    (128, True, W.TOP_P, 0.9, "htd"),
+    (128, False, W.TOP_K, 0.4, "thd"),
+    (64, True, W.TOP_K, 0.5, "thd"),
+    (64, False, W.TOP_P, 0.8, "htd"),
+])
+def test_ragged_last_blocks(ctx, oracle, S, causal, mode, param, layout):
+    """Sequence lengths that are not multiples of S (whole pooling windows): a block and a bit, several blocks and
+    most of one, less than one block, two and a half blocks."""
+    w = W.random_small(H=4, Hkv=2, lengths=(S + 8, 3 * S - 16, 40, 2 * S + S // 2), S=S, causal=causal, mode=mode,
+                       param=param, seed=13)
+    PU.full_pipeline_check(ctx, oracle, w, layout)
+
+
+def test_dense_attention_any_length(ctx, oracle):
+    """Attention alone needs no pooling windows: any length works."""
+    w = W.random_small(H=2, Hkv=1, lengths=(203, 1, 129), S=128, causal=True, seed=14)
+    q, k, v = PU.device_tensors(w)
+    qf, kf, vf = w.f32()
+    p = PU.problem_of(w)
+    o, lse = ctx.full_attn(p, q, k, v, want_lse=True)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, 128, True, None)
+    assert not np.isnan(o_ref).any()
+    PU.check_output(o.float().cpu().numpy(), o_ref, "dense")
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=1e-3, atol=2e-3)
+
+
 def test_planted_gqa_4k(ctx, oracle):
     w = W.gqa_planted(L=4096, H=8, Hkv=2, S=128, P=0.95, seed=21)
     PU.full_pipeline_check(ctx, oracle, w)
@@ -113,9 +141,9 @@ def test_softmax_scale_and_threshold_one(ctx, oracle):
 def test_error_paths(ctx):
     w = W.random_small(H=2, Hkv=1, lengths=(256,), S=128)
     q, k, v = PU.device_tensors(w)
-    bad = api.Problem([0, 200], 2, 1, 128, True)                 # length not a multiple of S
+    bad = api.Problem([0, 204], 2, 1, 128, True)                 # length not a multiple of c: no whole pooling windows
     with pytest.raises(api.UnisparseError) as e:
-        ctx.full_attn(bad, q, k, v)
+        ctx.build_mask(bad, api.Select(), q, k)
     assert e.value.code == 2
     p = PU.problem_of(w)
     with pytest.raises(api.UnisparseError) as e:
