@@ -181,3 +181,70 @@ def test_config2_shape_sampled_rows(ctx, oracle):
     heads = [0, 13, 31]
     o_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, 128, True, m_gpu, rows=rows[:4], heads=heads)
     PU.check_output(o_dev.float().cpu().numpy()[heads], o_ref[heads], "cfg2 sparse")
+
+
+def test_config3_headline_shape_sampled_rows(ctx, oracle):
+    """The benchmarked configuration itself (GQA 32/8, L = 128K, S = 128, Top-P 0.9): full GPU run of the mask,
+    the block-sparse and the dense kernel as bench.py launches them, oracle on sampled query-block rows."""
+    w = W.gqa_zipf()
+    N = w.n_blocks()[0]
+    rng = np.random.default_rng(3)
+    rows = sorted({0, 1, N - 1, *[int(x) for x in rng.integers(2, N - 1, 5)]})
+    q, k, v = PU.device_tensors(w)
+    qf, kf, vf = w.f32()
+    p, s = PU.problem_of(w), PU.select_of(w)
+    m_dev, sc_dev = ctx.build_mask(p, s, q, k, want_score=True)
+    torch.cuda.synchronize()
+    m_gpu = api.unpack_mask(m_dev, p.n_cols)
+    m_ref, sc_ref = oracle.build_mask(qf, kf, w.cu_seqlens, w.block_size, w.c_q, w.c_k, True, w.mode, w.param, rows=rows)
+    np.testing.assert_allclose(sc_dev.cpu().numpy()[:, rows], sc_ref[:, rows], rtol=2e-3, atol=1e-6)
+    PU.check_mask_against_oracle(m_gpu, m_ref, sc_ref, w.cu_seqlens, w.block_size, True, w.mode, w.param, rows)
+    # structure that holds at any size: nothing above the diagonal, no empty row, score rows sum to S / c_q
+    assert not np.triu(m_gpu, 1).any() and m_gpu.any(-1).all()
+    np.testing.assert_allclose(np.tril(sc_dev.cpu().numpy()).sum(-1), w.block_size / w.c_q, rtol=1e-3)
+    o_dev, _ = ctx.sparse_attn(p, q, k, v, m_dev)
+    od_dev, _ = ctx.full_attn(p, q, k, v)
+    torch.cuda.synchronize()
+    heads = [0, 13, 31]
+    att_rows = [rows[0], rows[3], rows[-1]]
+    o_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, w.block_size, True, m_gpu, rows=att_rows, heads=heads)
+    PU.check_output(o_dev.float().cpu().numpy()[heads], o_ref[heads], "cfg3 sparse")
+    od_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, w.block_size, True, None, rows=att_rows[1:], heads=heads[:2])
+    PU.check_output(od_dev.float().cpu().numpy()[heads[:2]], od_ref[heads[:2]], "cfg3 dense")
+
+
+def test_empty_sequences_in_the_batch(ctx, oracle):
+    """Zero-length sequences take no rows and change nothing for their neighbours."""
+    w = W.random_small(H=4, Hkv=2, lengths=(128, 0, 256, 0), S=128, causal=True, mode=W.TOP_P, param=0.9, seed=15)
+    PU.full_pipeline_check(ctx, oracle, w)
+    w2 = W.random_small(H=4, Hkv=2, lengths=(128, 256), S=128, causal=True, mode=W.TOP_P, param=0.9, seed=15)
+    assert np.array_equal(w.q, w2.q)                                  # same tokens, only the sequence table differs
+    q, k, v = PU.device_tensors(w)
+    m1, _ = ctx.build_mask(PU.problem_of(w), PU.select_of(w), q, k)
+    m2, _ = ctx.build_mask(PU.problem_of(w2), PU.select_of(w2), q, k)
+    o1, _ = ctx.sparse_attn(PU.problem_of(w), q, k, v, m1)
+    o2, _ = ctx.sparse_attn(PU.problem_of(w2), q, k, v, m2)
+    torch.cuda.synchronize()
+    assert torch.equal(m1, m2) and torch.equal(o1, o2)
+
+
+def test_maximum_block_count(ctx, oracle):
+    """One head at the largest supported sequence: 4096 blocks of 128 tokens (L = 512K).  Oracle on sampled rows."""
+    S, N = 128, 4096
+    w = W.random_small(H=1, Hkv=1, lengths=(N * S,), S=S, causal=True, mode=W.TOP_K, param=0.02, seed=16)
+    rows = [0, 1, 2047, N - 1]
+    q, k, v = PU.device_tensors(w)
+    qf, kf, vf = w.f32()
+    p, s = PU.problem_of(w), PU.select_of(w)
+    m_dev, sc_dev = ctx.build_mask(p, s, q, k, want_score=True)
+    torch.cuda.synchronize()
+    m_gpu = api.unpack_mask(m_dev, p.n_cols)
+    m_ref, sc_ref = oracle.build_mask(qf, kf, w.cu_seqlens, S, w.c_q, w.c_k, True, w.mode, w.param, rows=rows)
+    np.testing.assert_allclose(sc_dev.cpu().numpy()[:, rows], sc_ref[:, rows], rtol=2e-3, atol=1e-6)
+    PU.check_mask_against_oracle(m_gpu, m_ref, sc_ref, w.cu_seqlens, S, True, w.mode, w.param, rows)
+    k_i = np.maximum(1, np.ceil(0.02 * np.arange(1, N + 1)))
+    assert np.array_equal(m_gpu[0].sum(-1), k_i)                      # the budget is met exactly on every row
+    o_dev, _ = ctx.sparse_attn(p, q, k, v, m_dev)
+    torch.cuda.synchronize()
+    o_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, S, True, m_gpu, rows=[0, N - 1])
+    PU.check_output(o_dev.float().cpu().numpy(), o_ref, "max-size sparse")
