@@ -88,11 +88,11 @@ def _f32c(a) -> np.ndarray:
 # --------------------------------------------------------------------------- pooling
 
 def avgpool_seq(x: np.ndarray, c: int) -> np.ndarray:
-    """Eq. (1): x [L, d] float32 -> [L // c, d] composite tokens (bf16-valued float32)."""
+    """Eq. (1): x [L, d] float32 (one sequence) -> [ceil(L / c), d] composite tokens (bf16-valued float32)."""
     lib = _load()
     x = _f32c(x)
     L, d = x.shape
-    out = np.empty((L // c, d), dtype=np.float32)
+    out = np.empty((-(-L // c), d), dtype=np.float32)
     lib.oracle_avgpool_seq(_p(x, ctypes.c_float), L, d, c, _p(out, ctypes.c_float))
     return out
 
@@ -176,19 +176,32 @@ def _row_tables(cu_seqlens, S):
     return seq_of, loc_of, nb_of
 
 
+def composite_offsets(cu_seqlens, c: int):
+    """Packed offsets of the composite tokens: sequence b owns ceil(L_b / c) of them."""
+    off = [0]
+    for b in range(len(cu_seqlens) - 1):
+        off.append(off[-1] + -(-(int(cu_seqlens[b + 1]) - int(cu_seqlens[b])) // c))
+    return off
+
+
+def _pool_packed(X: np.ndarray, cu_seqlens, c: int) -> np.ndarray:
+    """Eq. (1) per sequence (windows never straddle sequences; a last window may be partial), packed again."""
+    return np.stack([np.concatenate([avgpool_seq(X[h, int(cu_seqlens[b]):int(cu_seqlens[b + 1])], c)
+                                     for b in range(len(cu_seqlens) - 1)]) for h in range(X.shape[0])])
+
+
 def composite_tokens(Q: np.ndarray, K: np.ndarray, cu_seqlens, c_q: int, c_k: int, c_h: int = 1):
     """Alg. 1 step 1 for a packed batch.
 
-    Returns (Qt [H', T/c_q, d], Kt [H', T/c_k, d]) with H' = H / c_h *query-side* compressed heads;
-    the keys are first repeated over the query heads of their group (query head h uses KV head
-    h // G), then pooled over heads exactly like the queries, so row h' of Kt pairs with row h' of Qt.
-    Windows never straddle sequences because every L_b is a multiple of c.
+    Returns (Qt [H', sum_b ceil(L_b/c_q), d], Kt [H', sum_b ceil(L_b/c_k), d]) with H' = H / c_h *query-side*
+    compressed heads; the keys are first repeated over the query heads of their group (query head h uses KV
+    head h // G), then pooled over heads exactly like the queries, so row h' of Kt pairs with row h' of Qt.
     """
     H, T, d = Q.shape
     Hkv = K.shape[0]
     G = H // Hkv
-    Qt = np.stack([avgpool_seq(Q[h], c_q) for h in range(H)])
-    Ktkv = np.stack([avgpool_seq(K[g], c_k) for g in range(Hkv)])
+    Qt = _pool_packed(Q, cu_seqlens, c_q)
+    Ktkv = _pool_packed(K, cu_seqlens, c_k)
     if c_h == 1:
         Kt = Ktkv[np.arange(H) // G]
         return Qt, Kt
@@ -212,15 +225,15 @@ def block_scores(Q: np.ndarray, K: np.ndarray, cu_seqlens: Sequence[int], S: int
     score = np.zeros((Hc, NQ, NK), dtype=np.float64)
     want = set(range(NQ)) if rows is None else set(int(r) for r in rows)
     cmode = (2 if literal_alg1 else 1) if causal else 0
+    oq, ok = composite_offsets(cu_seqlens, c_q), composite_offsets(cu_seqlens, c_k)
     row0 = 0
     for b in range(len(cu_seqlens) - 1):
         t0, t1 = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
-        assert (t1 - t0) % c_q == 0 and (t1 - t0) % c_k == 0, "partial pooling windows are not defined here"
         nb = -(-(t1 - t0) // S)
         loc = [i for i in range(nb) if (row0 + i) in want]
         if loc:
             for h in range(Hc):
-                sc = block_scores_head(Qt[h, t0 // c_q:t1 // c_q], Kt[h, t0 // c_k:t1 // c_k], S, c_q, c_k,
+                sc = block_scores_head(Qt[h, oq[b]:oq[b + 1]], Kt[h, ok[b]:ok[b + 1]], S, c_q, c_k,
                                        cmode, scale, loc)
                 if causal:                                   # Alg. 1 step 4, first line: drop j > i
                     for n, i in enumerate(loc):

@@ -44,20 +44,22 @@ float oracle_bf16_round_scalar(float x) { return oracle_round_bf16(x); }
 
 /*
  * Sequence-level average pooling, Eq. (1) / Alg. 1 step 1.
- *   x   : [L][d] tokens of one head
- *   out : [L/c][d] composite tokens; window t' covers tokens [t'c, t'c + c)
- * (0-based, non-overlapping windows).  Result quantised to bf16.
+ *   x   : [L][d] tokens of one head of one sequence
+ *   out : [ceil(L/c)][d] composite tokens; window t' covers tokens [t'c, t'c + c)
+ * (0-based, non-overlapping windows).  When c does not divide L the last window is
+ * clipped to the sequence and averages the tokens that exist.  Result quantised to bf16.
  */
 void oracle_avgpool_seq(const float *x, int64_t L, int d, int c, float *out)
 {
-    int64_t Lc = L / c;
+    int64_t Lc = (L + c - 1) / c;
     #pragma omp parallel for schedule(static)
     for (int64_t t = 0; t < Lc; ++t) {
+        int64_t cnt = (t + 1) * c <= L ? c : L - t * c;
         for (int e = 0; e < d; ++e) {
             float acc = 0.0f;
-            for (int m = 0; m < c; ++m)
+            for (int64_t m = 0; m < cnt; ++m)
                 acc = acc + x[(t * c + m) * (int64_t)d + e];
-            out[t * (int64_t)d + e] = oracle_round_bf16(acc / (float)c);
+            out[t * (int64_t)d + e] = oracle_round_bf16(acc / (float)cnt);
         }
     }
 }
@@ -87,7 +89,7 @@ void oracle_avgpool_head(const float *x, int H, int64_t Lc, int d, int c_h, floa
  * P~ = Q~ K~^T * scale (Sec. 4.3), row softmax over composite keys, then the
  * block aggregation of Eq. (3) with the index sets R_x(u) of Eq. (4).
  *
- *   qt : [Lq][d] composite queries (Lq = L/c_q),  kt : [Lk][d] composite keys
+ *   qt : [Lq][d] composite queries (Lq = ceil(L/c_q)),  kt : [Lk][d] composite keys
  *   rows[n_rows] : the query-block indices i whose score rows are wanted
  *   score : [n_rows][N] (N = L/S), score[r][j] = Score(rows[r], j)
  *

@@ -474,3 +474,66 @@ def test_ragged_packed_sequences_are_independent(oracle):
         Ob, _ = oracle.masked_attention(q[:, sl], k[:, sl], v[:, sl], [0, Lb], S, True, mb)
         assert np.array_equal(Ob, O[:, sl])
         r0 += nb
+
+
+# ----------------------------------------------------------------------------- partial pooling windows (c does not divide L)
+
+@pytest.mark.parametrize("c,L", [(8, 43), (4, 9), (16, 17), (32, 100)])
+def test_partial_window_pool_matches_torch_ceil_mode(oracle, c, L):
+    """The last window averages the tokens that exist: torch's avg_pool1d with ceil_mode (divisor = clipped window)."""
+    rng = np.random.default_rng(60 + c)
+    x = bf16_values(rng, (L, 128))
+    ref = torch.nn.functional.avg_pool1d(torch.from_numpy(x).T[None], c, c, ceil_mode=True)[0].T
+    ref = ref.to(torch.bfloat16).to(torch.float32).numpy()
+    got = oracle.avgpool_seq(x, c)
+    assert got.shape == (-(-L // c), 128)
+    assert np.array_equal(got, ref)
+    tail = x[(L // c) * c:].astype(np.float32)
+    if len(tail):                                                      # and by hand for the clipped window
+        acc = np.zeros(128, np.float32)
+        for row in tail:
+            acc = acc + row
+        hand = torch.from_numpy(acc / np.float32(len(tail))).to(torch.bfloat16).float().numpy()
+        assert np.array_equal(got[-1], hand)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_partial_window_scores_equal_attention_over_torch_pooled_tokens(oracle, causal):
+    """L = 2 blocks + 20 tokens with c = 8: 2 whole windows and one of 4 tokens in the last block."""
+    rng = np.random.default_rng(61)
+    L, d, S, c = 148, 64, 64, 8
+    q = bf16_values(rng, (1, L, d), 1.3)
+    k = bf16_values(rng, (1, L, d), 1.3)
+    pool = lambda x: torch.nn.functional.avg_pool1d(torch.from_numpy(x).T[None], c, c, ceil_mode=True)[0].T \
+        .to(torch.bfloat16).double()
+    pq, pk = pool(q[0]), pool(k[0])                                  # 19 composite tokens
+    p = pq @ pk.T / np.sqrt(d)
+    if causal:                                                       # c_q = c_k: composite key s' visible iff s' <= t'
+        p = p.masked_fill(torch.triu(torch.ones(19, 19, dtype=torch.bool), 1), float("-inf"))
+    a = torch.softmax(p, -1)
+    n, N = S // c, 3
+    pad = torch.zeros(N * n, N * n, dtype=torch.float64)
+    pad[:19, :19] = a
+    ref = pad.reshape(N, n, N, n).sum(dim=(1, 3)).numpy()
+    got = oracle.block_scores(q, k, [0, L], S, c, c, causal)[0]
+    if causal:
+        ref = np.tril(ref)
+    np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(got.sum(-1), [8, 8, 3], rtol=1e-12)
+
+
+def test_partial_windows_packed_sequences_are_independent(oracle):
+    rng = np.random.default_rng(62)
+    S, d, c = 16, 32, 8
+    lens = [37, 5, 50]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    q, k = [bf16_values(rng, (2, int(cu[-1]), d)) for _ in range(2)]
+    assert oracle.composite_offsets(cu, c) == [0, 5, 6, 13]
+    m, sc = oracle.build_mask(q, k, cu, S, c, c, True, 0, 0.8)
+    r0 = 0
+    for b, Lb in enumerate(lens):
+        sl = slice(int(cu[b]), int(cu[b + 1]))
+        nb = -(-Lb // S)
+        mb, sb = oracle.build_mask(q[:, sl], k[:, sl], [0, Lb], S, c, c, True, 0, 0.8)
+        assert np.array_equal(mb, m[:, r0:r0 + nb, :nb]) and np.array_equal(sb, sc[:, r0:r0 + nb, :nb])
+        r0 += nb
