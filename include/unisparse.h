@@ -20,8 +20,8 @@
  * - A problem is a packed batch of B sequences ("varlen"): tokens of all sequences are
  *   concatenated along the token axis, sequence b owning tokens [cu_seqlens[b], cu_seqlens[b+1]).
  *   Sequences never interact.  A length that is not a multiple of block_size gives a shorter last block
- *   (the block index sets of Eq. (4) clipped to the sequence); build_mask additionally needs every length
- *   to be a multiple of c_q and of c_k (whole pooling windows).
+ *   (the block index sets of Eq. (4) clipped to the sequence) and, when c does not divide it, a partial last
+ *   pooling window that averages the tokens that exist.
  * - Grouped-query attention: query head h uses key/value head h / (n_heads_q / n_heads_kv).
  * - Query-block rows are numbered over the packed batch: row r = (blocks of earlier sequences)
  *   + local block index i.  NQ = sum_b ceil(L_b / block_size) rows, NK = max_b ceil(L_b / block_size).
@@ -53,7 +53,7 @@ typedef struct unisparse_ctx unisparse_ctx;   /* opaque; caches device propertie
 typedef enum {
     UNISPARSE_OK = 0,
     UNISPARSE_ERR_NULL = 1,          /* a required pointer is NULL */
-    UNISPARSE_ERR_SHAPE = 2,         /* lengths not multiples of c, c not dividing block_size, head counts ... */
+    UNISPARSE_ERR_SHAPE = 2,         /* c not dividing block_size, head counts, misaligned tensors ... */
     UNISPARSE_ERR_PARAM = 3,         /* threshold / budget outside (0, 1], unknown mode ... */
     UNISPARSE_ERR_UNSUPPORTED = 4,   /* valid request this build has no kernel for */
     UNISPARSE_ERR_WORKSPACE = 5,     /* workspace smaller than unisparse_workspace_bytes() */
@@ -114,6 +114,17 @@ size_t unisparse_workspace_bytes(const unisparse_problem *p, const unisparse_sel
  */
 unisparse_status unisparse_avgpool_seq(unisparse_ctx *ctx, unisparse_tensor x, int32_t n_heads,
                                        int64_t total_tokens, int32_t c, void *out, void *stream);
+
+/*
+ * Eq. (1) for the packed batch of a problem whose lengths need not be multiples of c: sequence b yields
+ * ceil(L_b / c) composite tokens, windows never straddle sequences, and a last window that the sequence
+ * does not fill averages the tokens that exist (divisor = their number).  This is what build_mask
+ * applies internally.  Only num_seqs and cu_seqlens of the problem are used for the geometry.
+ *   x   : [total_tokens, n_heads, 128] view
+ *   out : DEVICE bf16 [n_heads][sum_b ceil(L_b / c)][128], contiguous
+ */
+unisparse_status unisparse_avgpool_seq_varlen(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor x,
+                                              int32_t n_heads, int32_t c, void *out, void *stream);
 
 /*
  * Alg. 1 steps 1-4: composite tokens, compressed softmax scores, block aggregation, selection.

@@ -24,6 +24,7 @@ HEAD_DIM = 128
 EXPORTS = [
     "unisparse_create", "unisparse_destroy", "unisparse_status_string", "unisparse_mask_row_words",
     "unisparse_mask_words", "unisparse_score_elems", "unisparse_workspace_bytes", "unisparse_avgpool_seq",
+    "unisparse_avgpool_seq_varlen",
     "unisparse_build_mask", "unisparse_select_blocks", "unisparse_sparse_attn", "unisparse_full_attn",
     "unisparse_attn",
 ]
@@ -77,6 +78,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
         getattr(lib, name).restype = sz
     lib.unisparse_avgpool_seq.argtypes = [vp, _Tensor, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp]
     lib.unisparse_avgpool_seq.restype = ctypes.c_int
+    lib.unisparse_avgpool_seq_varlen.argtypes = [vp, PP, _Tensor, ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.unisparse_avgpool_seq_varlen.restype = ctypes.c_int
     lib.unisparse_build_mask.argtypes = [vp, PP, SP, _Tensor, _Tensor, vp, sz, vp, vp, vp]
     lib.unisparse_build_mask.restype = ctypes.c_int
     lib.unisparse_select_blocks.argtypes = [vp, PP, SP, vp, vp, vp]
@@ -211,6 +214,13 @@ class Context:
         H = x.shape[1] if layout == "thd" else x.shape[0]
         out = torch.empty((H, T // c, HEAD_DIM), dtype=torch.bfloat16, device=x.device)
         _check(self.lib.unisparse_avgpool_seq(self.handle, _view(x, layout), H, T, c, out.data_ptr(), _stream()))
+        return out
+
+    def avgpool_seq_varlen(self, p: Problem, x: torch.Tensor, c: int, layout: str = "htd") -> torch.Tensor:
+        H = x.shape[1] if layout == "thd" else x.shape[0]
+        n_out = sum(-(-(int(p.cu_seqlens[b + 1]) - int(p.cu_seqlens[b])) // c) for b in range(len(p.cu_seqlens) - 1))
+        out = torch.empty((H, n_out, HEAD_DIM), dtype=torch.bfloat16, device=x.device)
+        _check(self.lib.unisparse_avgpool_seq_varlen(self.handle, p.c, _view(x, layout), H, c, out.data_ptr(), _stream()))
         return out
 
     def build_mask(self, p: Problem, s: Select, q: torch.Tensor, k: torch.Tensor, layout: str = "htd",

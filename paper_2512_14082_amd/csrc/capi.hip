@@ -65,10 +65,6 @@ unisparse_status check_select(const unisparse_problem *p, const unisparse_select
     if (s == nullptr) return UNISPARSE_ERR_NULL;
     if (s->c_q < 1 || s->c_k < 1 || s->c_h < 1) return UNISPARSE_ERR_PARAM;
     if (p->block_size % s->c_q != 0 || p->block_size % s->c_k != 0) return UNISPARSE_ERR_SHAPE;
-    for (int b = 0; b < p->num_seqs; ++b) {           // whole pooling windows only
-        const int64_t len = (int64_t)p->cu_seqlens[b + 1] - (int64_t)p->cu_seqlens[b];
-        if (len % s->c_q != 0 || len % s->c_k != 0) return UNISPARSE_ERR_SHAPE;
-    }
     int nq = p->block_size / s->c_q, nk = p->block_size / s->c_k;
     auto ok = [](int n) { return n == 4 || n == 8 || n == 16 || n == 32 || n == 64; };
     if (!ok(nq) || !ok(nk)) return UNISPARSE_ERR_UNSUPPORTED;
@@ -109,6 +105,22 @@ inline float scale_log2(const unisparse_problem *p)
     return sc * kLog2e;
 }
 
+// Packed offsets of the composite tokens (sequence b owns ceil(L_b / c) of them); returns their total and says
+// whether every window is whole (then the offsets are cu_tok / c and the flat pooling kernel applies).
+inline int64_t composite_offsets(const SeqTable &st, int c, int32_t *cu, bool *whole)
+{
+    int64_t tot = 0;
+    *whole = true;
+    for (int b = 0; b < st.num_seqs; ++b) {
+        const int len = st.cu_tok[b + 1] - st.cu_tok[b];
+        if (cu != nullptr) cu[b] = (int32_t)tot;
+        tot += (len + c - 1) / c;
+        if (len % c != 0) *whole = false;
+    }
+    if (cu != nullptr) cu[st.num_seqs] = (int32_t)tot;
+    return tot;
+}
+
 struct WsLayout {
     size_t qt, kt, qth, kth, score, total;
 };
@@ -119,10 +131,13 @@ WsLayout carve(const unisparse_problem *p, const unisparse_select *s, const Geom
     WsLayout w;
     size_t off = 0;
     const size_t row = (size_t)UNISPARSE_HEAD_DIM * 2;
-    w.qt = off; off += align256((size_t)p->n_heads_q * (g.T / s->c_q) * row);
-    w.kt = off; off += align256((size_t)p->n_heads_kv * (g.T / s->c_k) * row);
-    w.qth = off; if (s->c_h > 1) off += align256((size_t)hg.Hc * (g.T / s->c_q) * row);
-    w.kth = off; if (hg.kpool > 1) off += align256((size_t)hg.Hkc * (g.T / s->c_k) * row);
+    bool whole;
+    const size_t Tq = (size_t)composite_offsets(g.st, s->c_q, nullptr, &whole);
+    const size_t Tk = (size_t)composite_offsets(g.st, s->c_k, nullptr, &whole);
+    w.qt = off; off += align256((size_t)p->n_heads_q * Tq * row);
+    w.kt = off; off += align256((size_t)p->n_heads_kv * Tk * row);
+    w.qth = off; if (s->c_h > 1) off += align256((size_t)hg.Hc * Tq * row);
+    w.kth = off; if (hg.kpool > 1) off += align256((size_t)hg.Hkc * Tk * row);
     w.score = off; if (need_score) off += align256((size_t)hg.Hc * g.NQ * g.NK * sizeof(float));
     w.total = off;
     return w;
@@ -254,6 +269,21 @@ unisparse_status unisparse_avgpool_seq(unisparse_ctx *ctx, unisparse_tensor x, i
     return e == hipSuccess ? UNISPARSE_OK : UNISPARSE_ERR_HIP;
 }
 
+unisparse_status unisparse_avgpool_seq_varlen(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor x,
+                                              int32_t n_heads, int32_t c, void *out, void *stream)
+{
+    if (ctx == nullptr || out == nullptr) return UNISPARSE_ERR_NULL;
+    Geom g;
+    unisparse_status st;
+    if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(x)) != UNISPARSE_OK) return st;
+    if (n_heads < 1 || c < 1) return UNISPARSE_ERR_SHAPE;
+    if (((uintptr_t)out & 15) != 0) return UNISPARSE_ERR_SHAPE;
+    hipError_t e = launch_avgpool_seq_varlen(view(x), n_heads, g.st, c, reinterpret_cast<bf16_t *>(out),
+                                             (hipStream_t)stream);
+    return e == hipSuccess ? UNISPARSE_OK : UNISPARSE_ERR_HIP;
+}
+
 unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_problem *p, const unisparse_select *s,
                                       unisparse_tensor Q, unisparse_tensor K, void *workspace,
                                       size_t workspace_bytes, uint64_t *M, float *score, void *stream_)
@@ -266,7 +296,6 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     if ((st = check_select(p, s, &hg)) != UNISPARSE_OK) return st;
     if ((st = check_tensor(Q)) != UNISPARSE_OK) return st;
     if ((st = check_tensor(K)) != UNISPARSE_OK) return st;
-    // composite windows must not straddle sequences: guaranteed because c divides S and S divides every length
     const WsLayout w = carve(p, s, g, hg, score == nullptr);
     unsigned char *base = reinterpret_cast<unsigned char *>(align256((size_t)(uintptr_t)workspace));
     const size_t lead = (size_t)(base - reinterpret_cast<unsigned char *>(workspace));
@@ -276,22 +305,30 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
 
     bf16_t *qt = reinterpret_cast<bf16_t *>(base + w.qt);
     bf16_t *kt = reinterpret_cast<bf16_t *>(base + w.kt);
-    if (launch_avgpool_seq(view(Q), p->n_heads_q, g.T, s->c_q, qt, stream) != hipSuccess) return UNISPARSE_ERR_HIP;
-    if (launch_avgpool_seq(view(K), p->n_heads_kv, g.T, s->c_k, kt, stream) != hipSuccess) return UNISPARSE_ERR_HIP;
+    ProxyArgs pa;
+    bool whole_q, whole_k;
+    const int64_t Tq = composite_offsets(g.st, s->c_q, pa.cu_cq, &whole_q);
+    const int64_t Tk = composite_offsets(g.st, s->c_k, pa.cu_ck, &whole_k);
+    // windows never straddle sequences; with whole windows everywhere the packed batch pools as one flat array
+    hipError_t pe = whole_q ? launch_avgpool_seq(view(Q), p->n_heads_q, g.T, s->c_q, qt, stream)
+                            : launch_avgpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, qt, stream);
+    if (pe != hipSuccess) return UNISPARSE_ERR_HIP;
+    pe = whole_k ? launch_avgpool_seq(view(K), p->n_heads_kv, g.T, s->c_k, kt, stream)
+                 : launch_avgpool_seq_varlen(view(K), p->n_heads_kv, g.st, s->c_k, kt, stream);
+    if (pe != hipSuccess) return UNISPARSE_ERR_HIP;
     if (s->c_h > 1) {
         bf16_t *qth = reinterpret_cast<bf16_t *>(base + w.qth);
-        if (launch_avgpool_head(qt, p->n_heads_q, g.T / s->c_q, s->c_h, qth, stream) != hipSuccess)
+        if (launch_avgpool_head(qt, p->n_heads_q, Tq, s->c_h, qth, stream) != hipSuccess)
             return UNISPARSE_ERR_HIP;
         qt = qth;
         if (hg.kpool > 1) {
             bf16_t *kth = reinterpret_cast<bf16_t *>(base + w.kth);
-            if (launch_avgpool_head(kt, p->n_heads_kv, g.T / s->c_k, hg.kpool, kth, stream) != hipSuccess)
+            if (launch_avgpool_head(kt, p->n_heads_kv, Tk, hg.kpool, kth, stream) != hipSuccess)
                 return UNISPARSE_ERR_HIP;
             kt = kth;
         }
     }
     float *sc = score != nullptr ? score : reinterpret_cast<float *>(base + w.score);
-    ProxyArgs pa;
     pa.qt = qt;
     pa.kt = kt;
     pa.score = sc;

@@ -98,14 +98,19 @@ struct Launch {
 // ---- kernel launchers (defined one per .hip file) ------------------------------------------
 hipError_t launch_avgpool_seq(const TensorView &x, int n_heads, int64_t total_tokens, int c, bf16_t *out,
                               hipStream_t stream);
+// The same per sequence: sequence b owns ceil(L_b / c) composite tokens, its last window may be partial.
+hipError_t launch_avgpool_seq_varlen(const TensorView &x, int n_heads, const SeqTable &st, int c, bf16_t *out,
+                                     hipStream_t stream);
 hipError_t launch_avgpool_head(const bf16_t *x, int n_heads_in, int64_t tokens, int c_h, bf16_t *out,
                                hipStream_t stream);
 
 struct ProxyArgs {
-    const bf16_t *qt;        // [Hc][Tq][128] composite queries (Tq = T / c_q)
+    const bf16_t *qt;        // [Hc][Tq][128] composite queries (Tq = cu_cq[num_seqs])
     const bf16_t *kt;        // [Hkc][Tk][128] composite keys
     float *score;            // [Hc][NQ][NK]
     SeqTable st;
+    int32_t cu_cq[kMaxSeqs + 1];     // packed offsets of the composite queries / keys: sequence b owns
+    int32_t cu_ck[kMaxSeqs + 1];     // ceil(L_b / c) of them
     int32_t n_heads_q, n_heads_kv;   // (compressed) head counts
     int32_t S, c_q, c_k;
     int32_t causal;

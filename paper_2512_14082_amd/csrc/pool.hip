@@ -87,6 +87,63 @@ hipError_t launch_avgpool_seq(const TensorView &x, int n_heads, int64_t total_to
     return hipGetLastError();
 }
 
+// Eq. (1) for packed sequences of any length: composite token t of the packed output belongs to the sequence b
+// with cu_c[b] <= t < cu_c[b + 1] (cu_c accumulated on the fly), its window is clipped to that sequence and the
+// divisor is the number of tokens in it.
+__global__ __launch_bounds__(256) void avgpool_seq_varlen_kernel(const bf16_t *__restrict__ x, int64_t stride_tok,
+                                                                 int64_t stride_head, SeqTable st, int c,
+                                                                 int64_t tokens_out, int64_t n_items,
+                                                                 bf16_t *__restrict__ out)
+{
+    int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= n_items) return;
+    int chunk = (int)(gid & 15);
+    int64_t tt = gid >> 4;
+    int64_t t = tt % tokens_out;
+    int64_t h = tt / tokens_out;
+    int64_t base = 0;
+    int tok_first = 0, cnt = 0;
+    for (int b = 0; b < st.num_seqs; ++b) {
+        const int len = st.cu_tok[b + 1] - st.cu_tok[b];
+        const int nc = (len + c - 1) / c;
+        if (t < base + nc) {
+            const int w = (int)(t - base);
+            tok_first = st.cu_tok[b] + w * c;
+            cnt = min(c, len - w * c);
+            break;
+        }
+        base += nc;
+    }
+    const bf16_t *src = x + h * stride_head + (int64_t)tok_first * stride_tok + chunk * 8;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+    for (int m = 0; m < cnt; ++m) {
+        u32x4 w = *reinterpret_cast<const u32x4 *>(src + m * stride_tok);
+        float f[8];
+        unpack8(w, f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = acc[e] + f[e];
+    }
+    const float cf = (float)cnt;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = acc[e] / cf;
+    *reinterpret_cast<u32x4 *>(out + (h * tokens_out + t) * kHeadDim + chunk * 8) = pack8_rne(acc);
+}
+
+hipError_t launch_avgpool_seq_varlen(const TensorView &x, int n_heads, const SeqTable &st, int c, bf16_t *out,
+                                     hipStream_t stream)
+{
+    int64_t tokens_out = 0;
+    for (int b = 0; b < st.num_seqs; ++b) tokens_out += (st.cu_tok[b + 1] - st.cu_tok[b] + c - 1) / c;
+    int64_t n_items = (int64_t)n_heads * tokens_out * 16;
+    if (n_items == 0) return hipSuccess;
+    dim3 grid((unsigned)((n_items + 255) / 256)), block(256);
+    hipLaunchKernelGGL(avgpool_seq_varlen_kernel, grid, block, 0, stream, x.ptr, x.stride_tok, x.stride_head, st, c,
+                       tokens_out, n_items, out);
+    return hipGetLastError();
+}
+
 // out[h'][t][:] = bf16(mean over m < c_h of x[h' c_h + m][t][:]); x, out contiguous [heads][tokens][128].
 __global__ __launch_bounds__(256) void avgpool_head_kernel(const bf16_t *__restrict__ x, int64_t tokens, int c_h,
                                                            int64_t n_items, bf16_t *__restrict__ out)

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeo
     {
         int base = 0;
         for (int b = 0; b < a.st.num_seqs; ++b) {
-            int lq = (a.st.cu_tok[b + 1] - a.st.cu_tok[b]) / a.c_q;
+            int lq = a.cu_cq[b + 1] - a.cu_cq[b];
             int nt = (lq + rows_per_tile - 1) / rows_per_tile;
             if (tile < base + nt) { seq = b; qt = tile - base; break; }
             base += nt;
@@ -58,9 +58,9 @@ __global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeo
     }
     const int tok0 = a.st.cu_tok[seq];
     const int Lb = a.st.cu_tok[seq + 1] - tok0;
-    const int Lq = Lb / a.c_q, Lk = Lb / a.c_k;
+    const int Lq = a.cu_cq[seq + 1] - a.cu_cq[seq], Lk = a.cu_ck[seq + 1] - a.cu_ck[seq];   // a last window may be partial
     const int Nb = (Lb + a.S - 1) / a.S;                    // the last block may be a shorter remainder
-    const int64_t Tq = a.st.cu_tok[a.st.num_seqs] / a.c_q, Tk = a.st.cu_tok[a.st.num_seqs] / a.c_k;
+    const int64_t Tq = a.cu_cq[a.st.num_seqs], Tk = a.cu_ck[a.st.num_seqs];
     int row_base = 0;                                       // packed query-block row of the sequence's block 0
     for (int b = 0; b < seq; ++b) row_base += (a.st.cu_tok[b + 1] - a.st.cu_tok[b] + a.S - 1) / a.S;
 
@@ -91,12 +91,12 @@ __global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeo
     for (int qb = 0; qb < 2; ++qb) {
         int t = min(t0 + 32 * qb + lr, Lq - 1);
         lim_row[qb] = limit_of(t);
-        const bf16_t *src = a.qt + ((int64_t)head * Tq + tok0 / a.c_q + t) * kHeadDim + 8 * lh;
+        const bf16_t *src = a.qt + ((int64_t)head * Tq + a.cu_cq[seq] + t) * kHeadDim + 8 * lh;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qreg[qb][ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
     }
 
-    const bf16_t *kbase = a.kt + ((int64_t)kvh * Tk + tok0 / a.c_k) * kHeadDim;
+    const bf16_t *kbase = a.kt + ((int64_t)kvh * Tk + a.cu_ck[seq]) * kHeadDim;
     u32x4 pre[8];
     auto load_stage = [&](int st) {
 #pragma unroll
@@ -286,7 +286,7 @@ hipError_t launch_proxy_scores(const ProxyArgs &a, hipStream_t stream)
     const int rows_per_tile = kPxRowsPerWave * g.RC;
     g.n_tiles = 0;
     for (int b = 0; b < a.st.num_seqs; ++b) {
-        int lq = (a.st.cu_tok[b + 1] - a.st.cu_tok[b]) / a.c_q;
+        int lq = a.cu_cq[b + 1] - a.cu_cq[b];
         g.n_tiles += (lq + rows_per_tile - 1) / rows_per_tile;
     }
     int64_t nblk = (int64_t)a.n_heads_kv * g.GS * g.n_tiles;

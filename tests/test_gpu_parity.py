@@ -50,6 +50,20 @@ def test_ragged_last_blocks(ctx, oracle, S, causal, mode, param, layout):
     PU.full_pipeline_check(ctx, oracle, w, layout)
 
 
+@pytest.mark.parametrize("S,causal,cq,ck,layout", [
+    (128, True, 8, 8, "htd"),
+    (128, False, 4, 16, "thd"),
+    (64, True, 16, 4, "htd"),
+    (64, False, 8, 8, "thd"),
+])
+def test_partial_pooling_windows(ctx, oracle, S, causal, cq, ck, layout):
+    """Lengths that neither S nor c divides: the last pooling window of a sequence is partial."""
+    w = W.random_small(H=4, Hkv=2, lengths=(S + 5, 3 * S - 13, 37, 2 * S + S // 2 + 3, 1), S=S, causal=causal,
+                       mode=W.TOP_P, param=0.85, seed=17)
+    w.c_q, w.c_k = cq, ck
+    PU.full_pipeline_check(ctx, oracle, w, layout)
+
+
 def test_dense_attention_any_length(ctx, oracle):
     """Attention alone needs no pooling windows: any length works."""
     w = W.random_small(H=2, Hkv=1, lengths=(203, 1, 129), S=128, causal=True, seed=14)
@@ -141,9 +155,9 @@ def test_softmax_scale_and_threshold_one(ctx, oracle):
 def test_error_paths(ctx):
     w = W.random_small(H=2, Hkv=1, lengths=(256,), S=128)
     q, k, v = PU.device_tensors(w)
-    bad = api.Problem([0, 204], 2, 1, 128, True)                 # length not a multiple of c: no whole pooling windows
+    bad = api.Problem([0, 256], 3, 2, 128, True)                 # query heads not a multiple of key heads
     with pytest.raises(api.UnisparseError) as e:
-        ctx.build_mask(bad, api.Select(), q, k)
+        ctx.full_attn(bad, q, k, v)
     assert e.value.code == 2
     p = PU.problem_of(w)
     with pytest.raises(api.UnisparseError) as e:
