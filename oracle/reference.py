@@ -61,6 +61,8 @@ def _load():
     lib.oracle_bf16_round_scalar.restype = ctypes.c_float
     lib.oracle_avgpool_seq.argtypes = [f32p, i64, ci, ci, f32p]
     lib.oracle_avgpool_seq.restype = None
+    lib.oracle_maxpool_seq.argtypes = [f32p, i64, ci, ci, f32p]
+    lib.oracle_maxpool_seq.restype = None
     lib.oracle_avgpool_head.argtypes = [f32p, ci, i64, ci, ci, f32p]
     lib.oracle_avgpool_head.restype = None
     lib.oracle_block_scores.argtypes = [f32p, f32p, i64, i64, ci, ci, ci, ci, ci, ctypes.c_double,
@@ -95,6 +97,23 @@ def avgpool_seq(x: np.ndarray, c: int) -> np.ndarray:
     out = np.empty((-(-L // c), d), dtype=np.float32)
     lib.oracle_avgpool_seq(_p(x, ctypes.c_float), L, d, c, _p(out, ctypes.c_float))
     return out
+
+
+def maxpool_seq(x: np.ndarray, c: int) -> np.ndarray:
+    """Channel-wise maximum over the windows of Eq. (1) (ablation "Compression Strategy"): x [L, d] -> [ceil(L / c), d]."""
+    lib = _load()
+    x = _f32c(x)
+    L, d = x.shape
+    out = np.empty((-(-L // c), d), dtype=np.float32)
+    lib.oracle_maxpool_seq(_p(x, ctypes.c_float), L, d, c, _p(out, ctypes.c_float))
+    return out
+
+
+POOL_AVG, POOL_MAX = 0, 1
+
+
+def pool_seq(x: np.ndarray, c: int, pool: int = POOL_AVG) -> np.ndarray:
+    return maxpool_seq(x, c) if pool == POOL_MAX else avgpool_seq(x, c)
 
 
 def avgpool_head(x: np.ndarray, c_h: int) -> np.ndarray:
@@ -184,13 +203,14 @@ def composite_offsets(cu_seqlens, c: int):
     return off
 
 
-def _pool_packed(X: np.ndarray, cu_seqlens, c: int) -> np.ndarray:
+def _pool_packed(X: np.ndarray, cu_seqlens, c: int, pool: int = POOL_AVG) -> np.ndarray:
     """Eq. (1) per sequence (windows never straddle sequences; a last window may be partial), packed again."""
-    return np.stack([np.concatenate([avgpool_seq(X[h, int(cu_seqlens[b]):int(cu_seqlens[b + 1])], c)
+    return np.stack([np.concatenate([pool_seq(X[h, int(cu_seqlens[b]):int(cu_seqlens[b + 1])], c, pool)
                                      for b in range(len(cu_seqlens) - 1)]) for h in range(X.shape[0])])
 
 
-def composite_tokens(Q: np.ndarray, K: np.ndarray, cu_seqlens, c_q: int, c_k: int, c_h: int = 1):
+def composite_tokens(Q: np.ndarray, K: np.ndarray, cu_seqlens, c_q: int, c_k: int, c_h: int = 1,
+                     pool: int = POOL_AVG):
     """Alg. 1 step 1 for a packed batch.
 
     Returns (Qt [H', sum_b ceil(L_b/c_q), d], Kt [H', sum_b ceil(L_b/c_k), d]) with H' = H / c_h *query-side*
@@ -200,8 +220,8 @@ def composite_tokens(Q: np.ndarray, K: np.ndarray, cu_seqlens, c_q: int, c_k: in
     H, T, d = Q.shape
     Hkv = K.shape[0]
     G = H // Hkv
-    Qt = _pool_packed(Q, cu_seqlens, c_q)
-    Ktkv = _pool_packed(K, cu_seqlens, c_k)
+    Qt = _pool_packed(Q, cu_seqlens, c_q, pool)
+    Ktkv = _pool_packed(K, cu_seqlens, c_k, pool)
     if c_h == 1:
         Kt = Ktkv[np.arange(H) // G]
         return Qt, Kt
@@ -212,12 +232,12 @@ def composite_tokens(Q: np.ndarray, K: np.ndarray, cu_seqlens, c_q: int, c_k: in
 
 def block_scores(Q: np.ndarray, K: np.ndarray, cu_seqlens: Sequence[int], S: int, c_q: int, c_k: int,
                  causal: bool, scale: Optional[float] = None, c_h: int = 1,
-                 rows: Optional[Sequence[int]] = None, literal_alg1: bool = False) -> np.ndarray:
+                 rows: Optional[Sequence[int]] = None, literal_alg1: bool = False, pool: int = POOL_AVG) -> np.ndarray:
     """Alg. 1 steps 1-3 for a packed batch.  Returns float64 [H / c_h, NQ, NK]; only ``rows`` are filled."""
     H, T, d = Q.shape
     if scale is None:
         scale = 1.0 / np.sqrt(d)
-    Qt, Kt = composite_tokens(Q, K, cu_seqlens, c_q, c_k, c_h)
+    Qt, Kt = composite_tokens(Q, K, cu_seqlens, c_q, c_k, c_h, pool)
     Hc = Qt.shape[0]
     seq_of, loc_of, nb_of = _row_tables(cu_seqlens, S)
     NQ = len(seq_of)
@@ -245,9 +265,9 @@ def block_scores(Q: np.ndarray, K: np.ndarray, cu_seqlens: Sequence[int], S: int
 
 def build_mask(Q: np.ndarray, K: np.ndarray, cu_seqlens: Sequence[int], S: int, c_q: int, c_k: int,
                causal: bool, mode: int, param: float, scale: Optional[float] = None, c_h: int = 1,
-               rows: Optional[Sequence[int]] = None):
+               rows: Optional[Sequence[int]] = None, pool: int = POOL_AVG):
     """Alg. 1 steps 1-4 (+ head broadcast).  Returns (mask uint8 [H, NQ, NK], score float64 [H/c_h, NQ, NK])."""
-    score = block_scores(Q, K, cu_seqlens, S, c_q, c_k, causal, scale, c_h, rows)
+    score = block_scores(Q, K, cu_seqlens, S, c_q, c_k, causal, scale, c_h, rows, pool=pool)
     m = select_mask(score, cu_seqlens, S, causal, mode, param, rows)
     if c_h > 1:
         m = np.repeat(m, c_h, axis=0)                        # Broadcast_head

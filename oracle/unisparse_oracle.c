@@ -65,6 +65,28 @@ void oracle_avgpool_seq(const float *x, int64_t L, int d, int c, float *out)
 }
 
 /*
+ * Max pooling of the same windows (the alternative compression strategy of the ablation in
+ * Sec. 6 "Compression Strategy"): every channel keeps its largest value in the window.
+ * No rounding is involved: the result is one of the bf16 inputs.
+ */
+void oracle_maxpool_seq(const float *x, int64_t L, int d, int c, float *out)
+{
+    int64_t Lc = (L + c - 1) / c;
+    #pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < Lc; ++t) {
+        int64_t cnt = (t + 1) * c <= L ? c : L - t * c;
+        for (int e = 0; e < d; ++e) {
+            float best = x[(t * c) * (int64_t)d + e];
+            for (int64_t m = 1; m < cnt; ++m) {
+                float v = x[(t * c + m) * (int64_t)d + e];
+                if (v > best) best = v;
+            }
+            out[t * (int64_t)d + e] = best;
+        }
+    }
+}
+
+/*
  * Head-level average pooling, Eq. (2): mean of c_h consecutive heads of the
  * composite tokens.   x : [H][Lc][d]  ->  out : [H/c_h][Lc][d], quantised to bf16
  * (same quantisation rule as the sequence pooling).

@@ -537,3 +537,28 @@ def test_partial_windows_packed_sequences_are_independent(oracle):
         mb, sb = oracle.build_mask(q[:, sl], k[:, sl], [0, Lb], S, c, c, True, 0, 0.8)
         assert np.array_equal(mb, m[:, r0:r0 + nb, :nb]) and np.array_equal(sb, sc[:, r0:r0 + nb, :nb])
         r0 += nb
+
+
+# ----------------------------------------------------------------------------- max pooling (ablation "Compression Strategy")
+
+@pytest.mark.parametrize("c,L", [(8, 64), (8, 43), (4, 9), (32, 100)])
+def test_max_pool_matches_torch_max_pool(oracle, c, L):
+    rng = np.random.default_rng(70 + c)
+    x = bf16_values(rng, (L, 128))
+    ref = torch.nn.functional.max_pool1d(torch.from_numpy(x).T[None], c, c, ceil_mode=True)[0].T.numpy()
+    got = oracle.maxpool_seq(x, c)
+    assert np.array_equal(got, ref)
+    assert np.array_equal(oracle.maxpool_seq(x, 1), x)                        # c = 1 is the identity
+
+
+def test_max_pool_scores_equal_attention_over_torch_pooled_tokens(oracle):
+    rng = np.random.default_rng(71)
+    L, d, S, c = 256, 64, 64, 8
+    q = bf16_values(rng, (1, L, d), 1.3)
+    k = bf16_values(rng, (1, L, d), 1.3)
+    pool = lambda x: torch.nn.functional.max_pool1d(torch.from_numpy(x).T[None], c, c)[0].T.numpy()
+    ref = np.tril(brute_block_mass(pool(q[0]), pool(k[0]), S // c, True))
+    got = oracle.block_scores(q, k, [0, L], S, c, c, True, pool=oracle.POOL_MAX)[0]
+    np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-13)
+    avg = oracle.block_scores(q, k, [0, L], S, c, c, True)[0]
+    assert np.abs(avg - got).max() > 1e-3                                     # the option really changes the proxy
