@@ -81,6 +81,9 @@ typedef struct {
     int64_t stride_head;
 } unisparse_tensor;
 
+#define UNISPARSE_POOL_AVG 0
+#define UNISPARSE_POOL_MAX 1
+
 #define UNISPARSE_TOP_P 0            /* cumulative-score threshold, Eq. (5) */
 #define UNISPARSE_TOP_K 1            /* fixed budget: keep max(1, ceil(f * n_valid)) blocks per row */
 
@@ -92,6 +95,9 @@ typedef struct {
     int32_t mode;                    /* UNISPARSE_TOP_P or UNISPARSE_TOP_K */
     double threshold;                /* P in (0, 1]; P >= 1 keeps every valid block */
     double budget_frac;              /* f in (0, 1] */
+    int32_t pool;                    /* UNISPARSE_POOL_AVG (Eq. (1), the method) or UNISPARSE_POOL_MAX (channel-wise
+                                        maximum of the window: the alternative of the "Compression Strategy" ablation) */
+    int32_t reserved;                /* must be 0 */
 } unisparse_select;
 
 unisparse_status unisparse_create(unisparse_ctx **ctx, int device);
@@ -118,13 +124,13 @@ unisparse_status unisparse_avgpool_seq(unisparse_ctx *ctx, unisparse_tensor x, i
 /*
  * Eq. (1) for the packed batch of a problem whose lengths need not be multiples of c: sequence b yields
  * ceil(L_b / c) composite tokens, windows never straddle sequences, and a last window that the sequence
- * does not fill averages the tokens that exist (divisor = their number).  This is what build_mask
- * applies internally.  Only num_seqs and cu_seqlens of the problem are used for the geometry.
+ * does not fill averages the tokens that exist (divisor = their number).  pool = UNISPARSE_POOL_MAX takes
+ * the channel-wise maximum of the same windows instead.  This is what build_mask applies internally.  Only num_seqs and cu_seqlens of the problem are used for the geometry.
  *   x   : [total_tokens, n_heads, 128] view
  *   out : DEVICE bf16 [n_heads][sum_b ceil(L_b / c)][128], contiguous
  */
-unisparse_status unisparse_avgpool_seq_varlen(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor x,
-                                              int32_t n_heads, int32_t c, void *out, void *stream);
+unisparse_status unisparse_pool_seq_varlen(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor x,
+                                           int32_t n_heads, int32_t c, int32_t pool, void *out, void *stream);
 
 /*
  * Alg. 1 steps 1-4: composite tokens, compressed softmax scores, block aggregation, selection.

@@ -24,7 +24,7 @@ HEAD_DIM = 128
 EXPORTS = [
     "unisparse_create", "unisparse_destroy", "unisparse_status_string", "unisparse_mask_row_words",
     "unisparse_mask_words", "unisparse_score_elems", "unisparse_workspace_bytes", "unisparse_avgpool_seq",
-    "unisparse_avgpool_seq_varlen",
+    "unisparse_pool_seq_varlen",
     "unisparse_build_mask", "unisparse_select_blocks", "unisparse_sparse_attn", "unisparse_full_attn",
     "unisparse_attn",
 ]
@@ -48,7 +48,8 @@ class _Tensor(ctypes.Structure):
 
 class _Select(ctypes.Structure):
     _fields_ = [("c_q", ctypes.c_int32), ("c_k", ctypes.c_int32), ("c_h", ctypes.c_int32), ("mode", ctypes.c_int32),
-                ("threshold", ctypes.c_double), ("budget_frac", ctypes.c_double)]
+                ("threshold", ctypes.c_double), ("budget_frac", ctypes.c_double), ("pool", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 _lib = None
@@ -78,8 +79,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
         getattr(lib, name).restype = sz
     lib.unisparse_avgpool_seq.argtypes = [vp, _Tensor, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp]
     lib.unisparse_avgpool_seq.restype = ctypes.c_int
-    lib.unisparse_avgpool_seq_varlen.argtypes = [vp, PP, _Tensor, ctypes.c_int32, ctypes.c_int32, vp, vp]
-    lib.unisparse_avgpool_seq_varlen.restype = ctypes.c_int
+    lib.unisparse_pool_seq_varlen.argtypes = [vp, PP, _Tensor, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.unisparse_pool_seq_varlen.restype = ctypes.c_int
     lib.unisparse_build_mask.argtypes = [vp, PP, SP, _Tensor, _Tensor, vp, sz, vp, vp, vp]
     lib.unisparse_build_mask.restype = ctypes.c_int
     lib.unisparse_select_blocks.argtypes = [vp, PP, SP, vp, vp, vp]
@@ -144,10 +145,12 @@ class Select:
     mode: int = TOP_P
     threshold: float = 0.9
     budget_frac: float = 0.25
+    pool: int = 0          # 0 = average pooling (Eq. (1)), 1 = max pooling
 
     @property
     def c(self):
-        self._c = _Select(self.c_q, self.c_k, self.c_h, self.mode, float(self.threshold), float(self.budget_frac))
+        self._c = _Select(self.c_q, self.c_k, self.c_h, self.mode, float(self.threshold), float(self.budget_frac),
+                          self.pool, 0)
         return ctypes.byref(self._c)
 
 
@@ -216,11 +219,12 @@ class Context:
         _check(self.lib.unisparse_avgpool_seq(self.handle, _view(x, layout), H, T, c, out.data_ptr(), _stream()))
         return out
 
-    def avgpool_seq_varlen(self, p: Problem, x: torch.Tensor, c: int, layout: str = "htd") -> torch.Tensor:
+    def pool_seq_varlen(self, p: Problem, x: torch.Tensor, c: int, layout: str = "htd", pool: int = 0) -> torch.Tensor:
         H = x.shape[1] if layout == "thd" else x.shape[0]
         n_out = sum(-(-(int(p.cu_seqlens[b + 1]) - int(p.cu_seqlens[b])) // c) for b in range(len(p.cu_seqlens) - 1))
         out = torch.empty((H, n_out, HEAD_DIM), dtype=torch.bfloat16, device=x.device)
-        _check(self.lib.unisparse_avgpool_seq_varlen(self.handle, p.c, _view(x, layout), H, c, out.data_ptr(), _stream()))
+        _check(self.lib.unisparse_pool_seq_varlen(self.handle, p.c, _view(x, layout), H, c, pool, out.data_ptr(),
+                                                  _stream()))
         return out
 
     def build_mask(self, p: Problem, s: Select, q: torch.Tensor, k: torch.Tensor, layout: str = "htd",

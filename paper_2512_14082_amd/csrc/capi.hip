@@ -69,6 +69,7 @@ unisparse_status check_select(const unisparse_problem *p, const unisparse_select
     auto ok = [](int n) { return n == 4 || n == 8 || n == 16 || n == 32 || n == 64; };
     if (!ok(nq) || !ok(nk)) return UNISPARSE_ERR_UNSUPPORTED;
     if (s->mode != UNISPARSE_TOP_P && s->mode != UNISPARSE_TOP_K) return UNISPARSE_ERR_PARAM;
+    if ((s->pool != UNISPARSE_POOL_AVG && s->pool != UNISPARSE_POOL_MAX) || s->reserved != 0) return UNISPARSE_ERR_PARAM;
     if (s->mode == UNISPARSE_TOP_P && !(s->threshold > 0.0 && s->threshold <= 1.0)) return UNISPARSE_ERR_PARAM;
     if (s->mode == UNISPARSE_TOP_K && !(s->budget_frac > 0.0 && s->budget_frac <= 1.0)) return UNISPARSE_ERR_PARAM;
     if (p->n_heads_q % s->c_h != 0) return UNISPARSE_ERR_SHAPE;
@@ -264,13 +265,13 @@ unisparse_status unisparse_avgpool_seq(unisparse_ctx *ctx, unisparse_tensor x, i
     if (st != UNISPARSE_OK) return st;
     if (n_heads < 1 || total_tokens < 0 || c < 1 || total_tokens % c != 0) return UNISPARSE_ERR_SHAPE;
     if (((uintptr_t)out & 15) != 0) return UNISPARSE_ERR_SHAPE;
-    hipError_t e = launch_avgpool_seq(view(x), n_heads, total_tokens, c, reinterpret_cast<bf16_t *>(out),
+    hipError_t e = launch_avgpool_seq(view(x), n_heads, total_tokens, c, UNISPARSE_POOL_AVG, reinterpret_cast<bf16_t *>(out),
                                       (hipStream_t)stream);
     return e == hipSuccess ? UNISPARSE_OK : UNISPARSE_ERR_HIP;
 }
 
-unisparse_status unisparse_avgpool_seq_varlen(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor x,
-                                              int32_t n_heads, int32_t c, void *out, void *stream)
+unisparse_status unisparse_pool_seq_varlen(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor x,
+                                           int32_t n_heads, int32_t c, int32_t pool, void *out, void *stream)
 {
     if (ctx == nullptr || out == nullptr) return UNISPARSE_ERR_NULL;
     Geom g;
@@ -278,8 +279,9 @@ unisparse_status unisparse_avgpool_seq_varlen(unisparse_ctx *ctx, const unispars
     if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
     if ((st = check_tensor(x)) != UNISPARSE_OK) return st;
     if (n_heads < 1 || c < 1) return UNISPARSE_ERR_SHAPE;
+    if (pool != UNISPARSE_POOL_AVG && pool != UNISPARSE_POOL_MAX) return UNISPARSE_ERR_PARAM;
     if (((uintptr_t)out & 15) != 0) return UNISPARSE_ERR_SHAPE;
-    hipError_t e = launch_avgpool_seq_varlen(view(x), n_heads, g.st, c, reinterpret_cast<bf16_t *>(out),
+    hipError_t e = launch_avgpool_seq_varlen(view(x), n_heads, g.st, c, pool, reinterpret_cast<bf16_t *>(out),
                                              (hipStream_t)stream);
     return e == hipSuccess ? UNISPARSE_OK : UNISPARSE_ERR_HIP;
 }
@@ -310,11 +312,11 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     const int64_t Tq = composite_offsets(g.st, s->c_q, pa.cu_cq, &whole_q);
     const int64_t Tk = composite_offsets(g.st, s->c_k, pa.cu_ck, &whole_k);
     // windows never straddle sequences; with whole windows everywhere the packed batch pools as one flat array
-    hipError_t pe = whole_q ? launch_avgpool_seq(view(Q), p->n_heads_q, g.T, s->c_q, qt, stream)
-                            : launch_avgpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, qt, stream);
+    hipError_t pe = whole_q ? launch_avgpool_seq(view(Q), p->n_heads_q, g.T, s->c_q, s->pool, qt, stream)
+                            : launch_avgpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, s->pool, qt, stream);
     if (pe != hipSuccess) return UNISPARSE_ERR_HIP;
-    pe = whole_k ? launch_avgpool_seq(view(K), p->n_heads_kv, g.T, s->c_k, kt, stream)
-                 : launch_avgpool_seq_varlen(view(K), p->n_heads_kv, g.st, s->c_k, kt, stream);
+    pe = whole_k ? launch_avgpool_seq(view(K), p->n_heads_kv, g.T, s->c_k, s->pool, kt, stream)
+                 : launch_avgpool_seq_varlen(view(K), p->n_heads_kv, g.st, s->c_k, s->pool, kt, stream);
     if (pe != hipSuccess) return UNISPARSE_ERR_HIP;
     if (s->c_h > 1) {
         bf16_t *qth = reinterpret_cast<bf16_t *>(base + w.qth);

@@ -3,7 +3,8 @@
 // HBM-bound streaming kernels.  One thread owns 8 consecutive channels (16 bytes) of one composite
 // token, so the 16 threads of a token read one coalesced 256-byte row per source token.  The sum is
 // an fp32 sum in token (head) order followed by one fp32 division and one round-to-nearest-even to
-// bf16, which is bit-for-bit what a bf16 average pool defines.
+// bf16, which is bit-for-bit what a bf16 average pool defines.  With pool = UNISPARSE_POOL_MAX the same
+// windows are reduced by a channel-wise maximum instead (exact: the result is one of the inputs).
 #include "common.h"
 
 namespace us {
@@ -28,7 +29,7 @@ __device__ __forceinline__ u32x4 pack8_rne(const float *f)
 template <int C>
 __global__ __launch_bounds__(256) void avgpool_seq_kernel(const bf16_t *__restrict__ x, int64_t stride_tok,
                                                           int64_t stride_head, int64_t tokens_out, int c_rt,
-                                                          int64_t n_items, bf16_t *__restrict__ out)
+                                                          int pool, int64_t n_items, bf16_t *__restrict__ out)
 {
     const int c = C > 0 ? C : c_rt;
     int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -38,9 +39,10 @@ __global__ __launch_bounds__(256) void avgpool_seq_kernel(const bf16_t *__restri
     int64_t t = tt % tokens_out;
     int64_t h = tt / tokens_out;
     const bf16_t *src = x + h * stride_head + (t * c) * stride_tok + chunk * 8;
+    const bool pmax = pool == UNISPARSE_POOL_MAX;
     float acc[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+    for (int e = 0; e < 8; ++e) acc[e] = pmax ? -INFINITY : 0.0f;
     if (C > 0) {
         u32x4 w[C > 0 ? C : 1];
 #pragma unroll
@@ -50,7 +52,7 @@ __global__ __launch_bounds__(256) void avgpool_seq_kernel(const bf16_t *__restri
             float f[8];
             unpack8(w[m], f);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] = acc[e] + f[e];
+            for (int e = 0; e < 8; ++e) acc[e] = pmax ? fmaxf(acc[e], f[e]) : acc[e] + f[e];
         }
     } else {
         for (int m = 0; m < c; ++m) {
@@ -58,16 +60,16 @@ __global__ __launch_bounds__(256) void avgpool_seq_kernel(const bf16_t *__restri
             float f[8];
             unpack8(w, f);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] = acc[e] + f[e];
+            for (int e = 0; e < 8; ++e) acc[e] = pmax ? fmaxf(acc[e], f[e]) : acc[e] + f[e];
         }
     }
-    const float cf = (float)c;
+    const float cf = pmax ? 1.0f : (float)c;
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = acc[e] / cf;
     *reinterpret_cast<u32x4 *>(out + (h * tokens_out + t) * kHeadDim + chunk * 8) = pack8_rne(acc);
 }
 
-hipError_t launch_avgpool_seq(const TensorView &x, int n_heads, int64_t total_tokens, int c, bf16_t *out,
+hipError_t launch_avgpool_seq(const TensorView &x, int n_heads, int64_t total_tokens, int c, int pool, bf16_t *out,
                               hipStream_t stream)
 {
     int64_t tokens_out = total_tokens / c;
@@ -76,7 +78,7 @@ hipError_t launch_avgpool_seq(const TensorView &x, int n_heads, int64_t total_to
     dim3 grid((unsigned)((n_items + 255) / 256)), block(256);
 #define US_POOL(CC)                                                                                         \
     hipLaunchKernelGGL(avgpool_seq_kernel<CC>, grid, block, 0, stream, x.ptr, x.stride_tok, x.stride_head, \
-                       tokens_out, c, n_items, out)
+                       tokens_out, c, pool, n_items, out)
     switch (c) {
         case 4: US_POOL(4); break;
         case 8: US_POOL(8); break;
@@ -91,7 +93,7 @@ hipError_t launch_avgpool_seq(const TensorView &x, int n_heads, int64_t total_to
 // with cu_c[b] <= t < cu_c[b + 1] (cu_c accumulated on the fly), its window is clipped to that sequence and the
 // divisor is the number of tokens in it.
 __global__ __launch_bounds__(256) void avgpool_seq_varlen_kernel(const bf16_t *__restrict__ x, int64_t stride_tok,
-                                                                 int64_t stride_head, SeqTable st, int c,
+                                                                 int64_t stride_head, SeqTable st, int c, int pool,
                                                                  int64_t tokens_out, int64_t n_items,
                                                                  bf16_t *__restrict__ out)
 {
@@ -115,24 +117,25 @@ __global__ __launch_bounds__(256) void avgpool_seq_varlen_kernel(const bf16_t *_
         base += nc;
     }
     const bf16_t *src = x + h * stride_head + (int64_t)tok_first * stride_tok + chunk * 8;
+    const bool pmax = pool == UNISPARSE_POOL_MAX;
     float acc[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+    for (int e = 0; e < 8; ++e) acc[e] = pmax ? -INFINITY : 0.0f;
     for (int m = 0; m < cnt; ++m) {
         u32x4 w = *reinterpret_cast<const u32x4 *>(src + m * stride_tok);
         float f[8];
         unpack8(w, f);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = acc[e] + f[e];
+        for (int e = 0; e < 8; ++e) acc[e] = pmax ? fmaxf(acc[e], f[e]) : acc[e] + f[e];
     }
-    const float cf = (float)cnt;
+    const float cf = pmax ? 1.0f : (float)cnt;
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = acc[e] / cf;
     *reinterpret_cast<u32x4 *>(out + (h * tokens_out + t) * kHeadDim + chunk * 8) = pack8_rne(acc);
 }
 
-hipError_t launch_avgpool_seq_varlen(const TensorView &x, int n_heads, const SeqTable &st, int c, bf16_t *out,
-                                     hipStream_t stream)
+hipError_t launch_avgpool_seq_varlen(const TensorView &x, int n_heads, const SeqTable &st, int c, int pool,
+                                     bf16_t *out, hipStream_t stream)
 {
     int64_t tokens_out = 0;
     for (int b = 0; b < st.num_seqs; ++b) tokens_out += (st.cu_tok[b + 1] - st.cu_tok[b] + c - 1) / c;
@@ -140,7 +143,7 @@ hipError_t launch_avgpool_seq_varlen(const TensorView &x, int n_heads, const Seq
     if (n_items == 0) return hipSuccess;
     dim3 grid((unsigned)((n_items + 255) / 256)), block(256);
     hipLaunchKernelGGL(avgpool_seq_varlen_kernel, grid, block, 0, stream, x.ptr, x.stride_tok, x.stride_head, st, c,
-                       tokens_out, n_items, out);
+                       pool, tokens_out, n_items, out);
     return hipGetLastError();
 }
 

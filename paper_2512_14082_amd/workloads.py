@@ -57,6 +57,7 @@ class Workload:
     c_q: int = 8
     c_k: int = 8
     c_h: int = 1
+    pool: int = 0                 # 0 average pooling (the method), 1 max pooling (ablation)
     mode: int = TOP_P
     param: float = 0.9            # threshold P (TOP_P) or kept fraction f (TOP_K)
     gain: float = 4.0

@@ -262,3 +262,11 @@ def test_maximum_block_count(ctx, oracle):
     torch.cuda.synchronize()
     o_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, S, True, m_gpu, rows=[0, N - 1])
     PU.check_output(o_dev.float().cpu().numpy(), o_ref, "max-size sparse")
+
+
+@pytest.mark.parametrize("lengths", [(256, 384), (133, 37, 300)])
+def test_max_pooling_option(ctx, oracle, lengths):
+    """The max-pooling alternative of the compression-strategy ablation, whole and partial windows."""
+    w = W.random_small(H=4, Hkv=2, lengths=lengths, S=128, causal=True, mode=W.TOP_P, param=0.85, seed=18)
+    w.pool = 1
+    PU.full_pipeline_check(ctx, oracle, w, check_dense=False)
