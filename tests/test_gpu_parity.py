@@ -17,7 +17,7 @@ def ctx():
 
 
 def test_config1_single_head(ctx, oracle):
-    """BASELINE config 1 in full: L = 2048, S = 64, top-25 % budget."""
+    """Configuration 1 in full: one head, L = 2048, S = 64, top-25 % budget."""
     w = W.single_head_planted()
     agree = PU.full_pipeline_check(ctx, oracle, w)
     print("cfg1 mask agreement", agree)
