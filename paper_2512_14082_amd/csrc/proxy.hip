@@ -20,6 +20,25 @@ constexpr int kPxPitch = 272;              // bytes per LDS row: 256 + 16 keeps 
 constexpr int kPxStageBytes = kPxStageKeys * kPxPitch;
 constexpr int kPxRowsPerWave = 64;
 
+// Sum over aligned groups of R consecutive lanes (R = 4, 8, 16 or 32), result in every lane of the group: DPP
+// lane permutations inside a row of 16 lanes (no LDS traffic), one cross-row exchange for R = 32.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x)
+{
+    const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true);
+    return x + __int_as_float(y);
+}
+template <int R>
+__device__ __forceinline__ float group_sum(float x)
+{
+    if (R >= 32) x += __shfl_xor(x, 16, 64);
+    if (R >= 16) x = dpp_add<0x140>(x);      // row_mirror: lane l <-> 15 - l
+    if (R >= 8) x = dpp_add<0x141>(x);       // row_half_mirror: lane l <-> 7 - l inside each half row
+    x = dpp_add<0xB1>(x);                    // quad_perm [1, 0, 3, 2]
+    x = dpp_add<0x4E>(x);                    // quad_perm [2, 3, 0, 1]
+    return x;
+}
+
 struct ProxyGeom {
     int HG;          // query heads of one key head handled by a workgroup (1, 2 or 4)
     int RC;          // 64-row chunks per head in a workgroup (4 / HG)
@@ -194,8 +213,7 @@ __global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeo
                             for (int b = 0; b < NBK; ++b) {
                                 float x = bin[qb][b] * wnorm[qb];
                                 if (!kHalfBlocks) x += swap_half(x);
-#pragma unroll
-                                for (int off = 1; off < QR; off <<= 1) x += __shfl_xor(x, off, 64);
+                                x = group_sum<QR>(x);
                                 bin[qb][b] = x;
                             }
                         }
