@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--gain", type=float, default=4.0)
     ap.add_argument("--layout", default="htd", choices=["htd", "thd"])
+    ap.add_argument("--c-h", type=int, default=0, help="head compression factor (Eq. (2)); 0 = the workload's own (1)")
+    ap.add_argument("--c", type=int, default=0, help="sequence compression factor c_q = c_k; 0 = the workload's own (8)")
     ap.add_argument("--dense-reps", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--profile-copy-mb", type=int, default=0,
@@ -121,6 +123,10 @@ def main():
     t0 = time.time()
     w = W.by_name(args.workload, **kw)
     t_gen = time.time() - t0
+    if args.c_h > 0:
+        w.c_h = args.c_h
+    if args.c > 0:
+        w.c_q = w.c_k = args.c
     ctx = api.Context(0)
     q, k, v = (api.bits_to_device(x) for x in (w.q, w.k, w.v))
     if args.layout == "thd":
