@@ -270,3 +270,18 @@ def test_max_pooling_option(ctx, oracle, lengths):
     w = W.random_small(H=4, Hkv=2, lengths=lengths, S=128, causal=True, mode=W.TOP_P, param=0.85, seed=18)
     w.pool = 1
     PU.full_pipeline_check(ctx, oracle, w, check_dense=False)
+
+
+def test_one_call_entry_point_equals_two_calls(ctx, oracle):
+    """unisparse_attn = build_mask + sparse_attn on the same stream: same mask, same output, bit for bit."""
+    w = W.gqa_planted(L=2048, H=4, Hkv=2, S=128, P=0.9, seed=61)
+    q, k, v = PU.device_tensors(w)
+    p, s = PU.problem_of(w), PU.select_of(w)
+    m2, _ = ctx.build_mask(p, s, q, k)
+    o2, _ = ctx.sparse_attn(p, q, k, v, m2)
+    o1, m1 = ctx.attn(p, s, q, k, v)
+    torch.cuda.synchronize()
+    assert torch.equal(m1, m2) and torch.equal(o1, o2)
+    qf, kf, vf = w.f32()
+    o_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, 128, True, api.unpack_mask(m1, p.n_cols))
+    PU.check_output(o1.float().cpu().numpy(), o_ref, "one-call")
