@@ -47,7 +47,7 @@ struct ProxyGeom {
 };
 
 template <int NQB, int NKB, bool CAUSAL>
-__global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeom g)
+__global__ __launch_bounds__(kPxThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void proxy_kernel(ProxyArgs a, ProxyGeom g)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x;
@@ -138,8 +138,113 @@ __global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeo
     float l_run[2] = {0.0f, 0.0f};
     float mc[2] = {0.0f, 0.0f}, wnorm[2] = {0.0f, 0.0f};
 
-#pragma unroll 1
-    for (int pass = 0; pass < 2; ++pass) {
+    // ---- per-tile work, as separate pieces so that the MFMAs of one tile can run under the VALU work of another
+    // S^T of one 32-key tile for both query tiles (each K operand read feeds two MFMAs)
+    auto mfma_tile = [&](f32x16 (&dst)[2], const unsigned char *kb, int sub) __attribute__((always_inline)) {
+        f32x16 zero;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
+        const unsigned char *arow = kb + (32 * sub + lr) * kPxPitch + 16 * lh;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            bf16x8 ka = *reinterpret_cast<const bf16x8 *>(arow + 32 * ks);
+            dst[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[0][ks], ks == 0 ? zero : dst[0], 0, 0, 0);
+            dst[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[1][ks], ks == 0 ? zero : dst[1], 0, 0, 0);
+        }
+    };
+    // first sweep: running maximum and denominator of every composite query row
+    auto stats_tile = [&](const f32x16 (&src)[2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            float mx = src[qb][0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, src[qb][v]);
+            float m_new = fmaxf(m_run[qb], mx);
+            float m_safe = m_new == -INFINITY ? 0.0f : m_new;
+            float alpha = fast_exp2((m_run[qb] - m_safe) * c2);
+            float msc = m_safe * c2;
+            float sum = 0.0f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sum += fast_exp2(fmaf(src[qb][v], c2, -msc));
+            l_run[qb] = l_run[qb] * alpha + sum;
+            m_run[qb] = m_new;
+        }
+    };
+    // second sweep: normalised probabilities summed over the composite keys of each key block (registers),
+    // then over the composite queries of each query block (lanes), stored as Score(i, j)
+    auto bins_tile = [&](const f32x16 (&src)[2], int s_lo, int sub) __attribute__((always_inline)) {
+        // Key blocks against the registers of a 32-key tile: register v of a lane holds key
+        // 8 (v / 4) + 4 lh + v % 4.  n_k >= 8: a block is one or more groups of 8 keys, summed
+        // over both lane halves; n_k = 4: a block is the four keys of one lane half; n_k = 64: a
+        // block is two tiles, the second tile adds to what the first one stored.
+        constexpr bool kHalfBlocks = NKB == 4, kTwoTiles = NKB == 64;
+        constexpr int NBK = kHalfBlocks ? 4 : (NKB >= 32 ? 1 : 32 / NKB);   // bins per lane
+        constexpr int GPB = kHalfBlocks ? 1 : (NKB >= 32 ? 4 : NKB / 8);    // register groups per bin
+        constexpr int QR = NQB < 32 ? NQB : 32;                             // lanes of one query block
+        float bin[2][NBK];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+            for (int b = 0; b < NBK; ++b) bin[qb][b] = 0.0f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                bin[qb][(v >> 2) / GPB] += fast_exp2(fmaf(src[qb][v], c2, -mc[qb]));
+#pragma unroll
+            for (int b = 0; b < NBK; ++b) {
+                float x = bin[qb][b] * wnorm[qb];
+                if (!kHalfBlocks) x += swap_half(x);
+                x = group_sum<QR>(x);
+                bin[qb][b] = x;
+            }
+        }
+        if (NQB == 64) {                       // the wavefront's 64 rows are one query block
+#pragma unroll
+            for (int b = 0; b < NBK; ++b) bin[0][b] += bin[1][b];
+        }
+        if ((kHalfBlocks || lh == 0) && (lr % QR) == 0) {
+#pragma unroll
+            for (int qb = 0; qb < (NQB == 64 ? 1 : 2); ++qb) {
+                int t = t0 + 32 * qb + lr;
+                if (t < Lq) {
+                    int i = t / NQB;
+                    float *dst = a.score + ((int64_t)head * a.NQ + row_base + i) * a.NK;
+#pragma unroll
+                    for (int b = 0; b < NBK; ++b) {
+                        int j = kHalfBlocks ? s_lo / 4 + 2 * b + lh : s_lo / NKB + b;
+                        if (j < Nb) {
+                            if (kTwoTiles && (sub & 1)) dst[j] += bin[qb][b];
+                            else dst[j] = bin[qb][b];
+                        }
+                    }
+                }
+            }
+        }
+    };
+    // Software pipeline over the tiles that every row of the wavefront sees in full: the MFMAs of a tile are
+    // issued together with the VALU work of the tile before it (two sets of accumulators), across the stage
+    // barriers.  sA holds the tile whose VALU work is still pending.
+    f32x16 sA[2], sB[2];
+    bool pend = false;
+    int pend_slo = 0, pend_sub = 0;
+    auto valu_tile = [&](const f32x16 (&src)[2], auto pass_c, int s_lo, int sub) __attribute__((always_inline)) {
+        if constexpr (decltype(pass_c)::value == 0) stats_tile(src);
+        else bins_tile(src, s_lo, sub);
+    };
+    // one MFMA, its share of the VALU work, one operand read per two MFMAs - a hint for the machine scheduler
+    constexpr int MIXV = 4;
+    auto mix_hint = []() __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, MIXV, 0);   // VALU
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, MIXV, 0);
+        }
+    };
+
+    static_for<2>([&](auto pass_c) __attribute__((always_inline)) {
+        constexpr int pass = decltype(pass_c)::value;
         load_stage(0);
         __syncthreads();                                    // previous sweep finished reading LDS
         store_stage(0);
@@ -150,102 +255,60 @@ __global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeo
             if (more) load_stage(st + 1);
             const unsigned char *kb = lds + (st & 1) * kPxStageBytes;
             if (wave_active) {
-#pragma unroll 1
-                for (int sub = 0; sub < 4; ++sub) {
-                    const int s_lo = st * kPxStageKeys + 32 * sub;
-                    if (s_lo > lim_last) break;
-                    const bool partial = s_lo + 31 > lim_first;
-                    f32x16 sacc[2];
-#pragma unroll
-                    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) sacc[qb][v] = 0.0f;
-                    const unsigned char *arow = kb + (32 * sub + lr) * kPxPitch + 16 * lh;
-#pragma unroll
-                    for (int ks = 0; ks < 8; ++ks) {
-                        bf16x8 ka = *reinterpret_cast<const bf16x8 *>(arow + 32 * ks);
-                        sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[0][ks], sacc[0], 0, 0, 0);
-                        sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[1][ks], sacc[1], 0, 0, 0);
-                    }
-                    if (partial) {
-#pragma unroll
-                        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                            for (int v = 0; v < 16; ++v) {
-                                int key = s_lo + 8 * (v >> 2) + 4 * lh + (v & 3);
-                                sacc[qb][v] = key <= lim_row[qb] ? sacc[qb][v] : -INFINITY;
-                            }
-                    }
-                    if (pass == 0) {
-#pragma unroll
-                        for (int qb = 0; qb < 2; ++qb) {
-                            float mx = sacc[qb][0];
-#pragma unroll
-                            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sacc[qb][v]);
-                            float m_new = fmaxf(m_run[qb], mx);
-                            float m_safe = m_new == -INFINITY ? 0.0f : m_new;
-                            float alpha = fast_exp2((m_run[qb] - m_safe) * c2);
-                            float msc = m_safe * c2;
-                            float sum = 0.0f;
-#pragma unroll
-                            for (int v = 0; v < 16; ++v) sum += fast_exp2(fmaf(sacc[qb][v], c2, -msc));
-                            l_run[qb] = l_run[qb] * alpha + sum;
-                            m_run[qb] = m_new;
-                        }
+                const int s0 = st * kPxStageKeys;
+                if (s0 + kPxStageKeys - 1 <= lim_first) {   // all four tiles fully visible to all rows
+                    if (!pend) {
+                        mfma_tile(sB, kb, 0);
                     } else {
-                        // Key blocks against the registers of a 32-key tile: register v of a lane holds key
-                        // 8 (v / 4) + 4 lh + v % 4.  n_k >= 8: a block is one or more groups of 8 keys, summed
-                        // over both lane halves; n_k = 4: a block is the four keys of one lane half; n_k = 64: a
-                        // block is two tiles, the second tile adds to what the first one stored.
-                        constexpr bool kHalfBlocks = NKB == 4, kTwoTiles = NKB == 64;
-                        constexpr int NBK = kHalfBlocks ? 4 : (NKB >= 32 ? 1 : 32 / NKB);   // bins per lane
-                        constexpr int GPB = kHalfBlocks ? 1 : (NKB >= 32 ? 4 : NKB / 8);    // register groups per bin
-                        constexpr int QR = NQB < 32 ? NQB : 32;                             // lanes of one query block
-                        float bin[2][NBK];
+                        mfma_tile(sB, kb, 0);
+                        valu_tile(sA, pass_c, pend_slo, pend_sub);
+                        mix_hint();
+                    }
+                    mfma_tile(sA, kb, 1);
+                    valu_tile(sB, pass_c, s0, 0);
+                    mix_hint();
+                    mfma_tile(sB, kb, 2);
+                    valu_tile(sA, pass_c, s0 + 32, 1);
+                    mix_hint();
+                    mfma_tile(sA, kb, 3);
+                    valu_tile(sB, pass_c, s0 + 64, 2);
+                    mix_hint();
+                    pend = true;
+                    pend_slo = s0 + 96;
+                    pend_sub = 3;
+                } else {
+                    if (pend) {
+                        valu_tile(sA, pass_c, pend_slo, pend_sub);
+                        pend = false;
+                    }
+#pragma unroll 1
+                    for (int sub = 0; sub < 4; ++sub) {
+                        const int s_lo = s0 + 32 * sub;
+                        if (s_lo > lim_last) break;
+                        const bool partial = s_lo + 31 > lim_first;
+                        f32x16 sacc[2];
+                        mfma_tile(sacc, kb, sub);
+                        if (partial) {
 #pragma unroll
-                        for (int qb = 0; qb < 2; ++qb) {
+                            for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-                            for (int b = 0; b < NBK; ++b) bin[qb][b] = 0.0f;
-#pragma unroll
-                            for (int v = 0; v < 16; ++v)
-                                bin[qb][(v >> 2) / GPB] += fast_exp2(fmaf(sacc[qb][v], c2, -mc[qb]));
-#pragma unroll
-                            for (int b = 0; b < NBK; ++b) {
-                                float x = bin[qb][b] * wnorm[qb];
-                                if (!kHalfBlocks) x += swap_half(x);
-                                x = group_sum<QR>(x);
-                                bin[qb][b] = x;
-                            }
-                        }
-                        if (NQB == 64) {                       // the wavefront's 64 rows are one query block
-#pragma unroll
-                            for (int b = 0; b < NBK; ++b) bin[0][b] += bin[1][b];
-                        }
-                        if ((kHalfBlocks || lh == 0) && (lr % QR) == 0) {
-#pragma unroll
-                            for (int qb = 0; qb < (NQB == 64 ? 1 : 2); ++qb) {
-                                int t = t0 + 32 * qb + lr;
-                                if (t < Lq) {
-                                    int i = t / NQB;
-                                    float *dst = a.score + ((int64_t)head * a.NQ + row_base + i) * a.NK;
-#pragma unroll
-                                    for (int b = 0; b < NBK; ++b) {
-                                        int j = kHalfBlocks ? s_lo / 4 + 2 * b + lh : s_lo / NKB + b;
-                                        if (j < Nb) {
-                                            if (kTwoTiles && (sub & 1)) dst[j] += bin[qb][b];
-                                            else dst[j] = bin[qb][b];
-                                        }
-                                    }
+                                for (int v = 0; v < 16; ++v) {
+                                    int key = s_lo + 8 * (v >> 2) + 4 * lh + (v & 3);
+                                    sacc[qb][v] = key <= lim_row[qb] ? sacc[qb][v] : -INFINITY;
                                 }
-                            }
                         }
+                        valu_tile(sacc, pass_c, s_lo, sub);
                     }
                 }
             }
             if (more) store_stage((st + 1) & 1);
             __syncthreads();
         }
-        if (pass == 0) {
+        if (pend) {                                         // (not reached under causality: the last stage is partial)
+            valu_tile(sA, pass_c, pend_slo, pend_sub);
+            pend = false;
+        }
+        if constexpr (pass == 0) {
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
                 float m_o = swap_half(m_run[qb]), l_o = swap_half(l_run[qb]);
@@ -257,7 +320,7 @@ __global__ __launch_bounds__(kPxThreads) void proxy_kernel(ProxyArgs a, ProxyGeo
                 wnorm[qb] = t0 + 32 * qb + lr < Lq ? 1.0f / l_t : 0.0f;
             }
         }
-    }
+    });
 }
 
 static int proxy_pick_hg(int G)
