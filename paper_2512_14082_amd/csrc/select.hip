@@ -14,7 +14,7 @@ constexpr int kSelMaxN = UNISPARSE_MAX_BLOCKS_PER_SEQ;
 
 __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
 {
-    __shared__ uint64_t keys[kSelMaxN];
+    extern __shared__ uint64_t keys[];                    // next power of two >= NK entries (sized by the launcher)
     __shared__ double part[2][kSelThreads];
     __shared__ uint32_t bits[kSelMaxN / 32];
 
@@ -111,7 +111,9 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t stream)
 {
     int64_t n = (int64_t)a.n_heads_c * a.NQ;
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL(select_kernel, dim3((unsigned)n), dim3(kSelThreads), 0, stream, a);
+    int p2 = 1;
+    while (p2 < a.NK) p2 <<= 1;       // the sort works on a power of two; sizing LDS by it lets more workgroups share a CU
+    hipLaunchKernelGGL(select_kernel, dim3((unsigned)n), dim3(kSelThreads), (size_t)p2 * sizeof(uint64_t), stream, a);
     return hipGetLastError();
 }
 
