@@ -285,3 +285,29 @@ def test_one_call_entry_point_equals_two_calls(ctx, oracle):
     qf, kf, vf = w.f32()
     o_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, 128, True, api.unpack_mask(m1, p.n_cols))
     PU.check_output(o1.float().cpu().numpy(), o_ref, "one-call")
+
+
+def test_strided_views(ctx, oracle):
+    """Q, K, V and O as views into larger buffers: padded token and head strides, non-zero storage offset."""
+    w = W.random_small(H=4, Hkv=2, lengths=(256, 100), S=128, causal=True, mode=W.TOP_P, param=0.9, seed=19)
+    q, k, v = PU.device_tensors(w)                         # [H, T, d] contiguous
+    T = w.total_tokens
+
+    def padded(x):
+        big = torch.zeros((x.shape[0] + 1, T + 3, 128 + 24), dtype=torch.bfloat16, device="cuda")
+        view = big[1:, 2:2 + T, 8:136]                     # head stride, token stride 152, offset 8 elements
+        view.copy_(x)
+        return view
+
+    qp, kp, vp = padded(q), padded(k), padded(v)
+    p, s = PU.problem_of(w), PU.select_of(w)
+    m1, sc1 = ctx.build_mask(p, s, q, k, want_score=True)
+    m2, sc2 = ctx.build_mask(p, s, qp, kp, want_score=True)
+    o1, l1 = ctx.sparse_attn(p, q, k, v, m1, want_lse=True)
+    out = padded(torch.zeros_like(q))
+    o2, l2 = ctx.sparse_attn(p, qp, kp, vp, m2, out=out, want_lse=True)
+    d1, _ = ctx.full_attn(p, q, k, v)
+    d2, _ = ctx.full_attn(p, qp, kp, vp)
+    torch.cuda.synchronize()
+    assert torch.equal(m1, m2) and torch.equal(sc1, sc2)
+    assert torch.equal(o1, o2.contiguous()) and torch.equal(l1, l2) and torch.equal(d1, d2.contiguous())
