@@ -63,6 +63,8 @@ def _load():
     lib.oracle_avgpool_seq.restype = None
     lib.oracle_maxpool_seq.argtypes = [f32p, i64, ci, ci, f32p]
     lib.oracle_maxpool_seq.restype = None
+    lib.oracle_stochpool_seq.argtypes = [f32p, i64, ci, ci, f32p, f32p, i32p]
+    lib.oracle_stochpool_seq.restype = None
     lib.oracle_avgpool_head.argtypes = [f32p, ci, i64, ci, ci, f32p]
     lib.oracle_avgpool_head.restype = None
     lib.oracle_block_scores.argtypes = [f32p, f32p, i64, i64, ci, ci, ci, ci, ci, ctypes.c_double,
@@ -109,10 +111,28 @@ def maxpool_seq(x: np.ndarray, c: int) -> np.ndarray:
     return out
 
 
-POOL_AVG, POOL_MAX = 0, 1
+def stochpool_seq(x: np.ndarray, c: int, u: np.ndarray, return_choice: bool = False):
+    """Stochastic pooling (ablation "Compression Strategy"): one token per window, drawn by its share of the
+    window's L2 norms from the uniform numbers u [ceil(L / c)].  x [L, d] -> [ceil(L / c), d] (, offsets chosen)."""
+    lib = _load()
+    x = _f32c(x)
+    L, d = x.shape
+    Lc = -(-L // c)
+    u = _f32c(u)
+    assert u.shape == (Lc,)
+    out = np.empty((Lc, d), dtype=np.float32)
+    sel = np.empty(Lc, dtype=np.int32)
+    lib.oracle_stochpool_seq(_p(x, ctypes.c_float), L, d, c, _p(u, ctypes.c_float), _p(out, ctypes.c_float),
+                             _p(sel, ctypes.c_int32))
+    return (out, sel) if return_choice else out
 
 
-def pool_seq(x: np.ndarray, c: int, pool: int = POOL_AVG) -> np.ndarray:
+POOL_AVG, POOL_MAX, POOL_STOCHASTIC = 0, 1, 2
+
+
+def pool_seq(x: np.ndarray, c: int, pool: int = POOL_AVG, u: Optional[np.ndarray] = None) -> np.ndarray:
+    if pool == POOL_STOCHASTIC:
+        return stochpool_seq(x, c, u)
     return maxpool_seq(x, c) if pool == POOL_MAX else avgpool_seq(x, c)
 
 
@@ -203,14 +223,17 @@ def composite_offsets(cu_seqlens, c: int):
     return off
 
 
-def _pool_packed(X: np.ndarray, cu_seqlens, c: int, pool: int = POOL_AVG) -> np.ndarray:
-    """Eq. (1) per sequence (windows never straddle sequences; a last window may be partial), packed again."""
-    return np.stack([np.concatenate([pool_seq(X[h, int(cu_seqlens[b]):int(cu_seqlens[b + 1])], c, pool)
+def _pool_packed(X: np.ndarray, cu_seqlens, c: int, pool: int = POOL_AVG, u: Optional[np.ndarray] = None) -> np.ndarray:
+    """Eq. (1) per sequence (windows never straddle sequences; a last window may be partial), packed again.
+    u [heads, packed composite tokens]: the uniform numbers of stochastic pooling, laid out like the result."""
+    off = composite_offsets(cu_seqlens, c)
+    return np.stack([np.concatenate([pool_seq(X[h, int(cu_seqlens[b]):int(cu_seqlens[b + 1])], c, pool,
+                                              None if u is None else u[h, off[b]:off[b + 1]])
                                      for b in range(len(cu_seqlens) - 1)]) for h in range(X.shape[0])])
 
 
 def composite_tokens(Q: np.ndarray, K: np.ndarray, cu_seqlens, c_q: int, c_k: int, c_h: int = 1,
-                     pool: int = POOL_AVG):
+                     pool: int = POOL_AVG, rand=None):
     """Alg. 1 step 1 for a packed batch.
 
     Returns (Qt [H', sum_b ceil(L_b/c_q), d], Kt [H', sum_b ceil(L_b/c_k), d]) with H' = H / c_h *query-side*
@@ -220,8 +243,9 @@ def composite_tokens(Q: np.ndarray, K: np.ndarray, cu_seqlens, c_q: int, c_k: in
     H, T, d = Q.shape
     Hkv = K.shape[0]
     G = H // Hkv
-    Qt = _pool_packed(Q, cu_seqlens, c_q, pool)
-    Ktkv = _pool_packed(K, cu_seqlens, c_k, pool)
+    rq, rk = rand if rand is not None else (None, None)   # stochastic pooling: uniforms [H, Tq], [Hkv, Tk]
+    Qt = _pool_packed(Q, cu_seqlens, c_q, pool, rq)
+    Ktkv = _pool_packed(K, cu_seqlens, c_k, pool, rk)
     if c_h == 1:
         Kt = Ktkv[np.arange(H) // G]
         return Qt, Kt
@@ -232,12 +256,13 @@ def composite_tokens(Q: np.ndarray, K: np.ndarray, cu_seqlens, c_q: int, c_k: in
 
 def block_scores(Q: np.ndarray, K: np.ndarray, cu_seqlens: Sequence[int], S: int, c_q: int, c_k: int,
                  causal: bool, scale: Optional[float] = None, c_h: int = 1,
-                 rows: Optional[Sequence[int]] = None, literal_alg1: bool = False, pool: int = POOL_AVG) -> np.ndarray:
+                 rows: Optional[Sequence[int]] = None, literal_alg1: bool = False, pool: int = POOL_AVG,
+                 rand=None) -> np.ndarray:
     """Alg. 1 steps 1-3 for a packed batch.  Returns float64 [H / c_h, NQ, NK]; only ``rows`` are filled."""
     H, T, d = Q.shape
     if scale is None:
         scale = 1.0 / np.sqrt(d)
-    Qt, Kt = composite_tokens(Q, K, cu_seqlens, c_q, c_k, c_h, pool)
+    Qt, Kt = composite_tokens(Q, K, cu_seqlens, c_q, c_k, c_h, pool, rand)
     Hc = Qt.shape[0]
     seq_of, loc_of, nb_of = _row_tables(cu_seqlens, S)
     NQ = len(seq_of)
@@ -265,9 +290,9 @@ def block_scores(Q: np.ndarray, K: np.ndarray, cu_seqlens: Sequence[int], S: int
 
 def build_mask(Q: np.ndarray, K: np.ndarray, cu_seqlens: Sequence[int], S: int, c_q: int, c_k: int,
                causal: bool, mode: int, param: float, scale: Optional[float] = None, c_h: int = 1,
-               rows: Optional[Sequence[int]] = None, pool: int = POOL_AVG):
+               rows: Optional[Sequence[int]] = None, pool: int = POOL_AVG, rand=None):
     """Alg. 1 steps 1-4 (+ head broadcast).  Returns (mask uint8 [H, NQ, NK], score float64 [H/c_h, NQ, NK])."""
-    score = block_scores(Q, K, cu_seqlens, S, c_q, c_k, causal, scale, c_h, rows, pool=pool)
+    score = block_scores(Q, K, cu_seqlens, S, c_q, c_k, causal, scale, c_h, rows, pool=pool, rand=rand)
     m = select_mask(score, cu_seqlens, S, causal, mode, param, rows)
     if c_h > 1:
         m = np.repeat(m, c_h, axis=0)                        # Broadcast_head

@@ -87,6 +87,51 @@ void oracle_maxpool_seq(const float *x, int64_t L, int d, int c, float *out)
 }
 
 /*
+ * Stochastic pooling of the same windows (third compression strategy of the ablation in Sec. 6
+ * "Compression Strategy"): the composite token is ONE token of the window, token m drawn with
+ * probability  w_m / sum_m' w_m'  where the magnitude w_m = ||x_m||_2 is the Euclidean norm of the
+ * token's d channels.  The draw is made from a caller-supplied uniform number u[t'] in [0, 1) by
+ * inversion: the chosen m is the first one whose running sum w_0 + ... + w_m exceeds u * (total sum);
+ * if none does (all magnitudes zero) the last token of the window is taken.
+ *
+ * A floating-point comparison decides an index here, so the precision is part of the definition:
+ * fp32 throughout -- squares accumulated with fused multiply-adds in channel order, a correctly
+ * rounded square root, the running sum in token order, one product u * total.
+ *   sel (optional) : [ceil(L/c)] receives the chosen offsets m.
+ */
+void oracle_stochpool_seq(const float *x, int64_t L, int d, int c, const float *u, float *out, int32_t *sel)
+{
+    int64_t Lc = (L + c - 1) / c;
+    #pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < Lc; ++t) {
+        int64_t cnt = (t + 1) * c <= L ? c : L - t * c;
+        float total = 0.0f;
+        for (int64_t m = 0; m < cnt; ++m) {
+            float sq = 0.0f;
+            for (int e = 0; e < d; ++e) {
+                float v = x[(t * c + m) * (int64_t)d + e];
+                sq = fmaf(v, v, sq);
+            }
+            total = total + sqrtf(sq);
+        }
+        float cut = u[t] * total;
+        int64_t pick = cnt - 1;
+        float run = 0.0f;
+        for (int64_t m = 0; m < cnt; ++m) {
+            float sq = 0.0f;
+            for (int e = 0; e < d; ++e) {
+                float v = x[(t * c + m) * (int64_t)d + e];
+                sq = fmaf(v, v, sq);
+            }
+            run = run + sqrtf(sq);
+            if (run > cut) { pick = m; break; }
+        }
+        for (int e = 0; e < d; ++e) out[t * (int64_t)d + e] = x[(t * c + pick) * (int64_t)d + e];
+        if (sel) sel[t] = (int32_t)pick;
+    }
+}
+
+/*
  * Head-level average pooling, Eq. (2): mean of c_h consecutive heads of the
  * composite tokens.   x : [H][Lc][d]  ->  out : [H/c_h][Lc][d], quantised to bf16
  * (same quantisation rule as the sequence pooling).

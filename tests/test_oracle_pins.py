@@ -562,3 +562,96 @@ def test_max_pool_scores_equal_attention_over_torch_pooled_tokens(oracle):
     np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-13)
     avg = oracle.block_scores(q, k, [0, L], S, c, c, True)[0]
     assert np.abs(avg - got).max() > 1e-3                                     # the option really changes the proxy
+
+
+# ---- stochastic pooling (ablation "Compression Strategy"): one token per window, drawn by its share of the L2 norms
+
+def test_stochastic_pool_picks_tokens_in_proportion_to_their_norms(oracle):
+    # A window of tokens with norms 1, 2, 3, 6: over a fine grid of uniform numbers the choice frequencies are the
+    # normalised norms 1/12, 2/12, 3/12, 6/12 (squared norms would give 1/50, 4/50, 9/50, 36/50).
+    d, c, n = 16, 4, 12000
+    base = np.zeros((c, d), dtype=np.float32)
+    for m, w in enumerate((1.0, 2.0, 3.0, 6.0)):
+        base[m, m] = w                                                         # distinct directions, exact norms
+    x = np.tile(base, (n, 1))
+    u = ((np.arange(n) + 0.5) / n).astype(np.float32)
+    out, sel = oracle.stochpool_seq(x, c, u, return_choice=True)
+    freq = np.bincount(sel, minlength=c) / n
+    np.testing.assert_allclose(freq, np.array([1, 2, 3, 6]) / 12.0, atol=2.0 / n)
+    assert np.array_equal(out, base[sel])                                      # the composite IS the chosen token
+    # inversion: the chosen offsets are non-decreasing in u, ties broken towards the earlier token
+    assert np.all(np.diff(sel) >= 0)
+    assert sel[0] == 0 and sel[-1] == c - 1
+
+
+def test_stochastic_pool_closed_forms(oracle):
+    rng = np.random.default_rng(81)
+    d, c = 32, 8
+    # equal norms -> token floor(u c)
+    dirs = np.eye(d, dtype=np.float32)[:c] * 4.0
+    u = np.array([0.0, 0.124, 0.126, 0.5, 0.874, 0.876, 0.9999], dtype=np.float32)
+    x = np.tile(dirs, (len(u), 1))
+    _, sel = oracle.stochpool_seq(x, c, u, return_choice=True)
+    assert sel.tolist() == [0, 0, 1, 4, 6, 7, 7]
+    # all the magnitude on one token -> always that token; zero tokens are never drawn, whatever u
+    x = np.zeros((3 * c, d), dtype=np.float32)
+    x[5], x[c + 0], x[2 * c + 7] = 1.0, -2.0, 0.5
+    _, sel = oracle.stochpool_seq(x, c, np.array([0.0, 0.7, 0.3], dtype=np.float32), return_choice=True)
+    assert sel.tolist() == [5, 0, 7]
+    # the norm is over all channels and sign-blind: a token of many small channels outweighs one large channel
+    x = np.zeros((2, d), dtype=np.float32)
+    x[0, 3] = 3.0                                                              # norm 3
+    x[1, :] = -1.0                                                             # norm sqrt(32) = 5.66
+    share0 = 3.0 / (3.0 + np.sqrt(32.0))
+    _, sel = oracle.stochpool_seq(x, 2, np.array([share0 - 1e-3], dtype=np.float32), return_choice=True)
+    assert sel[0] == 0
+    _, sel = oracle.stochpool_seq(x, 2, np.array([share0 + 1e-3], dtype=np.float32), return_choice=True)
+    assert sel[0] == 1
+    # c = 1 is the identity; an all-zero window returns a zero token
+    y = bf16_values(rng, (20, d), 1.0)
+    assert np.array_equal(oracle.stochpool_seq(y, 1, rng.random(20).astype(np.float32)), y)
+    assert not oracle.stochpool_seq(np.zeros((8, d), np.float32), 4, np.array([0.3, 0.9], np.float32)).any()
+
+
+@pytest.mark.parametrize("L,c", [(37, 8), (64, 16), (5, 8)])
+def test_stochastic_pool_matches_fp64_inversion_and_clips_last_window(oracle, L, c):
+    # Independent statement in float64 numpy: cumulative norms against u * total.  A draw may differ only when u sits
+    # within fp32 rounding of a boundary between two tokens, which these seeded numbers avoid by a wide margin.
+    rng = np.random.default_rng(L * 100 + c)
+    d = 64
+    x = bf16_values(rng, (L, d), 1.0)
+    Lc = -(-L // c)
+    u = rng.random(Lc).astype(np.float32)
+    out, sel = oracle.stochpool_seq(x, c, u, return_choice=True)
+    for t in range(Lc):
+        win = x[t * c:min(L, (t + 1) * c)].astype(np.float64)
+        cum = np.cumsum(np.sqrt((win ** 2).sum(axis=1)))
+        margin = np.abs(cum / cum[-1] - float(u[t])).min()
+        assert margin > 1e-5
+        pick = int(np.searchsorted(cum, float(u[t]) * cum[-1], side="right"))
+        assert sel[t] == pick and pick < len(win)
+        assert np.array_equal(out[t], x[t * c + pick])
+
+
+def test_stochastic_pool_feeds_the_proxy_per_head_and_sequence(oracle):
+    # composite tokens of a packed batch: every (head, sequence) window uses its own uniform number, laid out like
+    # the packed composite tokens; scores equal exact attention over the tokens picked by hand.
+    rng = np.random.default_rng(83)
+    cu, d, S, c = [0, 128, 320], 32, 64, 8
+    T = cu[-1]
+    q = bf16_values(rng, (2, T, d), 1.2)
+    k = bf16_values(rng, (1, T, d), 1.2)
+    off = oracle.composite_offsets(cu, c)
+    rq = rng.random((2, off[-1])).astype(np.float32)
+    rk = rng.random((1, off[-1])).astype(np.float32)
+    Qt, Kt = oracle.composite_tokens(q, k, cu, c, c, 1, oracle.POOL_STOCHASTIC, (rq, rk))
+    for h in range(2):
+        for b in range(2):
+            ref = oracle.stochpool_seq(q[h, cu[b]:cu[b + 1]], c, rq[h, off[b]:off[b + 1]])
+            assert np.array_equal(Qt[h, off[b]:off[b + 1]], ref)
+    assert np.array_equal(Kt[0], Kt[1])                                        # one KV head serves both query heads
+    got = oracle.block_scores(q, k, cu, S, c, c, True, pool=oracle.POOL_STOCHASTIC, rand=(rq, rk))
+    for b in range(2):
+        nb = (cu[b + 1] - cu[b]) // S
+        ref = np.tril(brute_block_mass(Qt[0, off[b]:off[b + 1]], Kt[0, off[b]:off[b + 1]], S // c, True))
+        np.testing.assert_allclose(got[0, cu[b] // S:cu[b] // S + nb, :nb], ref, rtol=1e-10, atol=1e-13)
