@@ -83,6 +83,7 @@ typedef struct {
 
 #define UNISPARSE_POOL_AVG 0
 #define UNISPARSE_POOL_MAX 1
+#define UNISPARSE_POOL_STOCHASTIC 2
 
 #define UNISPARSE_TOP_P 0            /* cumulative-score threshold, Eq. (5) */
 #define UNISPARSE_TOP_K 1            /* fixed budget: keep max(1, ceil(f * n_valid)) blocks per row */
@@ -95,9 +96,15 @@ typedef struct {
     int32_t mode;                    /* UNISPARSE_TOP_P or UNISPARSE_TOP_K */
     double threshold;                /* P in (0, 1]; P >= 1 keeps every valid block */
     double budget_frac;              /* f in (0, 1] */
-    int32_t pool;                    /* UNISPARSE_POOL_AVG (Eq. (1), the method) or UNISPARSE_POOL_MAX (channel-wise
-                                        maximum of the window: the alternative of the "Compression Strategy" ablation) */
+    int32_t pool;                    /* UNISPARSE_POOL_AVG (Eq. (1), the method), or one of the alternatives of the
+                                        "Compression Strategy" ablation: UNISPARSE_POOL_MAX (channel-wise maximum of
+                                        the window) or UNISPARSE_POOL_STOCHASTIC (one token of the window, drawn by
+                                        its share of the window's L2 norms; see unisparse_pool_seq_varlen) */
     int32_t reserved;                /* must be 0 */
+    const float *rand_q;             /* UNISPARSE_POOL_STOCHASTIC only (else ignored): DEVICE uniform numbers in [0, 1), */
+    const float *rand_k;             /* one per composite token: rand_q [H][sum_b ceil(L_b/c_q)],
+                                        rand_k [H_kv][sum_b ceil(L_b/c_k)], laid out like the composite tokens.
+                                        Borrowed for the call; the library draws no random numbers itself. */
 } unisparse_select;
 
 unisparse_status unisparse_create(unisparse_ctx **ctx, int device);
@@ -125,12 +132,22 @@ unisparse_status unisparse_avgpool_seq(unisparse_ctx *ctx, unisparse_tensor x, i
  * Eq. (1) for the packed batch of a problem whose lengths need not be multiples of c: sequence b yields
  * ceil(L_b / c) composite tokens, windows never straddle sequences, and a last window that the sequence
  * does not fill averages the tokens that exist (divisor = their number).  pool = UNISPARSE_POOL_MAX takes
- * the channel-wise maximum of the same windows instead.  This is what build_mask applies internally.  Only num_seqs and cu_seqlens of the problem are used for the geometry.
- *   x   : [total_tokens, n_heads, 128] view
- *   out : DEVICE bf16 [n_heads][sum_b ceil(L_b / c)][128], contiguous
+ * the channel-wise maximum of the same windows instead.  pool = UNISPARSE_POOL_STOCHASTIC copies ONE token
+ * of the window: token m with probability w_m / sum_m' w_m', w_m = the L2 norm of the token's 128 channels,
+ * drawn by inversion of rand[h][t'] -- the first m whose running sum w_0 + ... + w_m exceeds
+ * rand * (w_0 + ... + w_{cnt-1}), the last token of the window if none does.  That comparison is taken in
+ * fp32 (squares accumulated by fused multiply-adds in channel order, correctly rounded square root, sums in
+ * token order), so equal inputs and equal random numbers give equal choices everywhere; c <= 32.
+ * This is what build_mask applies internally.  Only num_seqs and cu_seqlens of the problem are used for
+ * the geometry.
+ *   x    : [total_tokens, n_heads, 128] view
+ *   rand : DEVICE float [n_heads][sum_b ceil(L_b / c)] in [0, 1); read only for UNISPARSE_POOL_STOCHASTIC
+ *          (NULL otherwise); UNISPARSE_ERR_NULL if missing
+ *   out  : DEVICE bf16 [n_heads][sum_b ceil(L_b / c)][128], contiguous
  */
 unisparse_status unisparse_pool_seq_varlen(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor x,
-                                           int32_t n_heads, int32_t c, int32_t pool, void *out, void *stream);
+                                           int32_t n_heads, int32_t c, int32_t pool, const float *rand, void *out,
+                                           void *stream);
 
 /*
  * Alg. 1 steps 1-4: composite tokens, compressed softmax scores, block aggregation, selection.

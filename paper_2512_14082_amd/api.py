@@ -49,7 +49,7 @@ class _Tensor(ctypes.Structure):
 class _Select(ctypes.Structure):
     _fields_ = [("c_q", ctypes.c_int32), ("c_k", ctypes.c_int32), ("c_h", ctypes.c_int32), ("mode", ctypes.c_int32),
                 ("threshold", ctypes.c_double), ("budget_frac", ctypes.c_double), ("pool", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("reserved", ctypes.c_int32), ("rand_q", ctypes.c_void_p), ("rand_k", ctypes.c_void_p)]
 
 
 _lib = None
@@ -79,7 +79,7 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
         getattr(lib, name).restype = sz
     lib.unisparse_avgpool_seq.argtypes = [vp, _Tensor, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp]
     lib.unisparse_avgpool_seq.restype = ctypes.c_int
-    lib.unisparse_pool_seq_varlen.argtypes = [vp, PP, _Tensor, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.unisparse_pool_seq_varlen.argtypes = [vp, PP, _Tensor, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp]
     lib.unisparse_pool_seq_varlen.restype = ctypes.c_int
     lib.unisparse_build_mask.argtypes = [vp, PP, SP, _Tensor, _Tensor, vp, sz, vp, vp, vp]
     lib.unisparse_build_mask.restype = ctypes.c_int
@@ -145,13 +145,23 @@ class Select:
     mode: int = TOP_P
     threshold: float = 0.9
     budget_frac: float = 0.25
-    pool: int = 0          # 0 = average pooling (Eq. (1)), 1 = max pooling
+    pool: int = 0          # 0 = average pooling (Eq. (1)), 1 = max pooling, 2 = stochastic pooling
+    rand_q: Optional[torch.Tensor] = None   # stochastic pooling: float32 device uniforms [H, composite queries]
+    rand_k: Optional[torch.Tensor] = None   # and [H_kv, composite keys]
 
     @property
     def c(self):
         self._c = _Select(self.c_q, self.c_k, self.c_h, self.mode, float(self.threshold), float(self.budget_frac),
-                          self.pool, 0)
+                          self.pool, 0, _rand_ptr(self.rand_q), _rand_ptr(self.rand_k))
         return ctypes.byref(self._c)
+
+
+def _rand_ptr(r: Optional[torch.Tensor]):
+    if r is None:
+        return None
+    if not r.is_cuda or r.dtype != torch.float32 or not r.is_contiguous():
+        raise ValueError("expected a contiguous float32 device tensor of uniform numbers")
+    return r.data_ptr()
 
 
 def _view(t: torch.Tensor, layout: str) -> _Tensor:
@@ -219,12 +229,13 @@ class Context:
         _check(self.lib.unisparse_avgpool_seq(self.handle, _view(x, layout), H, T, c, out.data_ptr(), _stream()))
         return out
 
-    def pool_seq_varlen(self, p: Problem, x: torch.Tensor, c: int, layout: str = "htd", pool: int = 0) -> torch.Tensor:
+    def pool_seq_varlen(self, p: Problem, x: torch.Tensor, c: int, layout: str = "htd", pool: int = 0,
+                        rand: Optional[torch.Tensor] = None) -> torch.Tensor:
         H = x.shape[1] if layout == "thd" else x.shape[0]
         n_out = sum(-(-(int(p.cu_seqlens[b + 1]) - int(p.cu_seqlens[b])) // c) for b in range(len(p.cu_seqlens) - 1))
         out = torch.empty((H, n_out, HEAD_DIM), dtype=torch.bfloat16, device=x.device)
-        _check(self.lib.unisparse_pool_seq_varlen(self.handle, p.c, _view(x, layout), H, c, pool, out.data_ptr(),
-                                                  _stream()))
+        _check(self.lib.unisparse_pool_seq_varlen(self.handle, p.c, _view(x, layout), H, c, pool, _rand_ptr(rand),
+                                                  out.data_ptr(), _stream()))
         return out
 
     def build_mask(self, p: Problem, s: Select, q: torch.Tensor, k: torch.Tensor, layout: str = "htd",

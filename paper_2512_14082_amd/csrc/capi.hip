@@ -69,7 +69,8 @@ unisparse_status check_select(const unisparse_problem *p, const unisparse_select
     auto ok = [](int n) { return n == 4 || n == 8 || n == 16 || n == 32 || n == 64; };
     if (!ok(nq) || !ok(nk)) return UNISPARSE_ERR_UNSUPPORTED;
     if (s->mode != UNISPARSE_TOP_P && s->mode != UNISPARSE_TOP_K) return UNISPARSE_ERR_PARAM;
-    if ((s->pool != UNISPARSE_POOL_AVG && s->pool != UNISPARSE_POOL_MAX) || s->reserved != 0) return UNISPARSE_ERR_PARAM;
+    if (s->pool < UNISPARSE_POOL_AVG || s->pool > UNISPARSE_POOL_STOCHASTIC || s->reserved != 0) return UNISPARSE_ERR_PARAM;
+    if (s->pool == UNISPARSE_POOL_STOCHASTIC && (s->rand_q == nullptr || s->rand_k == nullptr)) return UNISPARSE_ERR_NULL;
     if (s->mode == UNISPARSE_TOP_P && !(s->threshold > 0.0 && s->threshold <= 1.0)) return UNISPARSE_ERR_PARAM;
     if (s->mode == UNISPARSE_TOP_K && !(s->budget_frac > 0.0 && s->budget_frac <= 1.0)) return UNISPARSE_ERR_PARAM;
     if (p->n_heads_q % s->c_h != 0) return UNISPARSE_ERR_SHAPE;
@@ -271,7 +272,8 @@ unisparse_status unisparse_avgpool_seq(unisparse_ctx *ctx, unisparse_tensor x, i
 }
 
 unisparse_status unisparse_pool_seq_varlen(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor x,
-                                           int32_t n_heads, int32_t c, int32_t pool, void *out, void *stream)
+                                           int32_t n_heads, int32_t c, int32_t pool, const float *rand, void *out,
+                                           void *stream)
 {
     if (ctx == nullptr || out == nullptr) return UNISPARSE_ERR_NULL;
     Geom g;
@@ -279,10 +281,15 @@ unisparse_status unisparse_pool_seq_varlen(unisparse_ctx *ctx, const unisparse_p
     if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
     if ((st = check_tensor(x)) != UNISPARSE_OK) return st;
     if (n_heads < 1 || c < 1) return UNISPARSE_ERR_SHAPE;
-    if (pool != UNISPARSE_POOL_AVG && pool != UNISPARSE_POOL_MAX) return UNISPARSE_ERR_PARAM;
+    if (pool < UNISPARSE_POOL_AVG || pool > UNISPARSE_POOL_STOCHASTIC) return UNISPARSE_ERR_PARAM;
     if (((uintptr_t)out & 15) != 0) return UNISPARSE_ERR_SHAPE;
-    hipError_t e = launch_avgpool_seq_varlen(view(x), n_heads, g.st, c, pool, reinterpret_cast<bf16_t *>(out),
-                                             (hipStream_t)stream);
+    if (pool == UNISPARSE_POOL_STOCHASTIC && rand == nullptr) return UNISPARSE_ERR_NULL;
+    if (pool == UNISPARSE_POOL_STOCHASTIC && c > 32) return UNISPARSE_ERR_UNSUPPORTED;
+    hipError_t e = pool == UNISPARSE_POOL_STOCHASTIC
+                       ? launch_stochpool_seq_varlen(view(x), n_heads, g.st, c, rand, reinterpret_cast<bf16_t *>(out),
+                                                     (hipStream_t)stream)
+                       : launch_avgpool_seq_varlen(view(x), n_heads, g.st, c, pool, reinterpret_cast<bf16_t *>(out),
+                                                   (hipStream_t)stream);
     return e == hipSuccess ? UNISPARSE_OK : UNISPARSE_ERR_HIP;
 }
 
@@ -312,11 +319,14 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     const int64_t Tq = composite_offsets(g.st, s->c_q, pa.cu_cq, &whole_q);
     const int64_t Tk = composite_offsets(g.st, s->c_k, pa.cu_ck, &whole_k);
     // windows never straddle sequences; with whole windows everywhere the packed batch pools as one flat array
-    hipError_t pe = whole_q ? launch_avgpool_seq(view(Q), p->n_heads_q, g.T, s->c_q, s->pool, qt, stream)
-                            : launch_avgpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, s->pool, qt, stream);
+    const bool stoch = s->pool == UNISPARSE_POOL_STOCHASTIC;
+    hipError_t pe = stoch     ? launch_stochpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, s->rand_q, qt, stream)
+                    : whole_q ? launch_avgpool_seq(view(Q), p->n_heads_q, g.T, s->c_q, s->pool, qt, stream)
+                              : launch_avgpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, s->pool, qt, stream);
     if (pe != hipSuccess) return UNISPARSE_ERR_HIP;
-    pe = whole_k ? launch_avgpool_seq(view(K), p->n_heads_kv, g.T, s->c_k, s->pool, kt, stream)
-                 : launch_avgpool_seq_varlen(view(K), p->n_heads_kv, g.st, s->c_k, s->pool, kt, stream);
+    pe = stoch     ? launch_stochpool_seq_varlen(view(K), p->n_heads_kv, g.st, s->c_k, s->rand_k, kt, stream)
+         : whole_k ? launch_avgpool_seq(view(K), p->n_heads_kv, g.T, s->c_k, s->pool, kt, stream)
+                   : launch_avgpool_seq_varlen(view(K), p->n_heads_kv, g.st, s->c_k, s->pool, kt, stream);
     if (pe != hipSuccess) return UNISPARSE_ERR_HIP;
     if (s->c_h > 1) {
         bf16_t *qth = reinterpret_cast<bf16_t *>(base + w.qth);

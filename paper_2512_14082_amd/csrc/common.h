@@ -101,6 +101,8 @@ hipError_t launch_avgpool_seq(const TensorView &x, int n_heads, int64_t total_to
 // The same per sequence: sequence b owns ceil(L_b / c) composite tokens, its last window may be partial.
 hipError_t launch_avgpool_seq_varlen(const TensorView &x, int n_heads, const SeqTable &st, int c, int pool,
                                      bf16_t *out, hipStream_t stream);
+hipError_t launch_stochpool_seq_varlen(const TensorView &x, int n_heads, const SeqTable &st, int c, const float *u,
+                                       bf16_t *out, hipStream_t stream);
 hipError_t launch_avgpool_head(const bf16_t *x, int n_heads_in, int64_t tokens, int c_h, bf16_t *out,
                                hipStream_t stream);
 

@@ -147,6 +147,88 @@ hipError_t launch_avgpool_seq_varlen(const TensorView &x, int n_heads, const Seq
     return hipGetLastError();
 }
 
+// Stochastic pooling of the windows of Eq. (1) (third strategy of the ablation "Compression Strategy"): the composite
+// token is one token of its window, token m drawn with probability ||x_m||_2 / sum_m' ||x_m'||_2 by inversion of the
+// caller's uniform number u[h][t].  A comparison decides an index, so the arithmetic is pinned down: fp32 squares
+// accumulated by fused multiply-adds in channel order, a correctly rounded square root, the running sum in token
+// order, and the first m with (w_0 + ... + w_m) > u * total wins (the last token if none does).
+//
+// 16 lanes serve one window.  Lane l computes the norms of tokens l and l + 16 of the window, each over the 128
+// channels in order (so no cross-lane reduction touches the rounding), the 16 lanes exchange them, every lane
+// repeats the same running sum, and the group then copies the chosen 256-byte row, 16 bytes per lane.
+__device__ __forceinline__ float token_norm(const bf16_t *row)
+{
+    float sq = 0.0f;
+#pragma unroll 4
+    for (int k = 0; k < kHeadDim / 8; ++k) {
+        u32x4 w = *reinterpret_cast<const u32x4 *>(row + k * 8);
+        float f[8];
+        unpack8(w, f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sq = __builtin_fmaf(f[e], f[e], sq);
+    }
+    return __builtin_sqrtf(sq);          // IEEE square root (hipcc rounds fp32 sqrt correctly by default)
+}
+
+__global__ __launch_bounds__(256) void stochpool_seq_varlen_kernel(const bf16_t *__restrict__ x, int64_t stride_tok,
+                                                                   int64_t stride_head, SeqTable st, int c,
+                                                                   const float *__restrict__ u, int64_t tokens_out,
+                                                                   int64_t n_items, bf16_t *__restrict__ out)
+{
+    int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= n_items) return;                     // n_items is a multiple of 16: groups leave together
+    int lane16 = (int)(gid & 15);
+    int64_t tt = gid >> 4;
+    int64_t t = tt % tokens_out;
+    int64_t h = tt / tokens_out;
+    int64_t base = 0;
+    int tok_first = 0, cnt = 0;
+    for (int b = 0; b < st.num_seqs; ++b) {
+        const int len = st.cu_tok[b + 1] - st.cu_tok[b];
+        const int nc = (len + c - 1) / c;
+        if (t < base + nc) {
+            const int w = (int)(t - base);
+            tok_first = st.cu_tok[b] + w * c;
+            cnt = min(c, len - w * c);
+            break;
+        }
+        base += nc;
+    }
+    if (cnt <= 0) return;                           // cannot happen for t < tokens_out; the whole group agrees
+    const bf16_t *src = x + h * stride_head + (int64_t)tok_first * stride_tok;
+    float w0 = lane16 < cnt ? token_norm(src + (int64_t)lane16 * stride_tok) : 0.0f;
+    float w1 = lane16 + 16 < cnt ? token_norm(src + (int64_t)(lane16 + 16) * stride_tok) : 0.0f;
+    float total = 0.0f;
+    for (int m = 0; m < cnt; ++m) total = total + __shfl(m < 16 ? w0 : w1, m & 15, 16);
+    const float cut = u[h * tokens_out + t] * total;
+    int pick = cnt - 1;
+    float run = 0.0f;
+    bool found = false;
+    for (int m = 0; m < cnt; ++m) {
+        run = run + __shfl(m < 16 ? w0 : w1, m & 15, 16);
+        if (!found && run > cut) {
+            pick = m;
+            found = true;
+        }
+    }
+    u32x4 row = *reinterpret_cast<const u32x4 *>(src + (int64_t)pick * stride_tok + lane16 * 8);
+    *reinterpret_cast<u32x4 *>(out + (h * tokens_out + t) * kHeadDim + lane16 * 8) = row;
+}
+
+hipError_t launch_stochpool_seq_varlen(const TensorView &x, int n_heads, const SeqTable &st, int c, const float *u,
+                                       bf16_t *out, hipStream_t stream)
+{
+    if (c > 32) return hipErrorInvalidValue;        // two tokens per lane
+    int64_t tokens_out = 0;
+    for (int b = 0; b < st.num_seqs; ++b) tokens_out += (st.cu_tok[b + 1] - st.cu_tok[b] + c - 1) / c;
+    int64_t n_items = (int64_t)n_heads * tokens_out * 16;
+    if (n_items == 0) return hipSuccess;
+    dim3 grid((unsigned)((n_items + 255) / 256)), block(256);
+    hipLaunchKernelGGL(stochpool_seq_varlen_kernel, grid, block, 0, stream, x.ptr, x.stride_tok, x.stride_head, st, c,
+                       u, tokens_out, n_items, out);
+    return hipGetLastError();
+}
+
 // out[h'][t][:] = bf16(mean over m < c_h of x[h' c_h + m][t][:]); x, out contiguous [heads][tokens][128].
 __global__ __launch_bounds__(256) void avgpool_head_kernel(const bf16_t *__restrict__ x, int64_t tokens, int c_h,
                                                            int64_t n_items, bf16_t *__restrict__ out)

@@ -57,7 +57,9 @@ class Workload:
     c_q: int = 8
     c_k: int = 8
     c_h: int = 1
-    pool: int = 0                 # 0 average pooling (the method), 1 max pooling (ablation)
+    pool: int = 0                 # 0 average pooling (the method), 1 max / 2 stochastic pooling (ablation)
+    rand_q: Optional[np.ndarray] = None   # stochastic pooling: float32 uniforms [H, composite queries]
+    rand_k: Optional[np.ndarray] = None   # and [H_kv, composite keys], see draw_pool_uniforms
     mode: int = TOP_P
     param: float = 0.9            # threshold P (TOP_P) or kept fraction f (TOP_K)
     gain: float = 4.0
@@ -93,6 +95,19 @@ class Workload:
 
     def f32(self):
         return bf16_bits_to_f32(self.q), bf16_bits_to_f32(self.k), bf16_bits_to_f32(self.v)
+
+    def n_composite(self, c: int) -> int:
+        """Composite tokens of the packed batch at compression factor c (one per started window)."""
+        return sum(-(-(self.cu_seqlens[b + 1] - self.cu_seqlens[b]) // c) for b in range(len(self.cu_seqlens) - 1))
+
+    def draw_pool_uniforms(self, seed: Optional[int] = None) -> "Workload":
+        """Switch to stochastic pooling and draw the uniform numbers in [0, 1) that it consumes, one per
+        (head, composite token), laid out like the composite tokens."""
+        rng = np.random.default_rng(self.seed + 977 if seed is None else seed)
+        self.pool = 2
+        self.rand_q = rng.random((self.n_heads_q, self.n_composite(self.c_q)), dtype=np.float32)
+        self.rand_k = rng.random((self.n_heads_kv, self.n_composite(self.c_k)), dtype=np.float32)
+        return self
 
 
 def _unit(rng, d):

@@ -27,8 +27,13 @@ def problem_of(w: W.Workload, scale=0.0):
 
 
 def select_of(w: W.Workload):
+    dev = lambda r: None if r is None else torch.from_numpy(r).cuda()
     return api.Select(w.c_q, w.c_k, w.c_h, w.mode, w.param if w.mode == W.TOP_P else 0.9,
-                      w.param if w.mode == W.TOP_K else 0.25, w.pool)
+                      w.param if w.mode == W.TOP_K else 0.25, w.pool, dev(w.rand_q), dev(w.rand_k))
+
+
+def rand_of(w: W.Workload):
+    return None if w.rand_q is None else (w.rand_q, w.rand_k)
 
 
 def row_geometry(cu, S):
@@ -96,13 +101,15 @@ def full_pipeline_check(ctx, oracle, w: W.Workload, layout="htd", check_dense=Tr
     p, s = problem_of(w), select_of(w)
     param = w.param
     # -- pooling: bit exact
-    qt = ctx.pool_seq_varlen(p, q, w.c_q, layout, w.pool)  # equals the flat entry point when every window is whole
+    qt = ctx.pool_seq_varlen(p, q, w.c_q, layout, w.pool, s.rand_q)  # equals the flat entry point when every window is whole
     if w.pool == 0 and all((w.cu_seqlens[b + 1] - w.cu_seqlens[b]) % w.c_q == 0 for b in range(len(w.cu_seqlens) - 1)):
         assert torch.equal(qt, ctx.avgpool_seq(q, w.c_q, layout))
     torch.cuda.synchronize()
     qt_bits = qt.view(torch.int16).cpu().numpy().view(np.uint16)
+    off = oracle.composite_offsets(w.cu_seqlens, w.c_q)
     for h in range(w.n_heads_q):
-        ref = np.concatenate([oracle.pool_seq(qf[h, w.cu_seqlens[b]:w.cu_seqlens[b + 1]], w.c_q, w.pool)
+        ref = np.concatenate([oracle.pool_seq(qf[h, w.cu_seqlens[b]:w.cu_seqlens[b + 1]], w.c_q, w.pool,
+                                              None if w.rand_q is None else w.rand_q[h, off[b]:off[b + 1]])
                               for b in range(len(w.cu_seqlens) - 1)])
         assert np.array_equal(qt_bits[h], W.f32_to_bf16_bits(ref)), f"pooling mismatch head {h}"
     # -- scores and mask
@@ -111,7 +118,7 @@ def full_pipeline_check(ctx, oracle, w: W.Workload, layout="htd", check_dense=Tr
     m_gpu = api.unpack_mask(m_dev, p.n_cols)
     sc_gpu = sc_dev.cpu().numpy()
     m_ref, sc_ref = oracle.build_mask(qf, kf, w.cu_seqlens, w.block_size, w.c_q, w.c_k, w.causal, w.mode, param,
-                                      c_h=w.c_h, rows=rows, pool=w.pool)
+                                      c_h=w.c_h, rows=rows, pool=w.pool, rand=rand_of(w))
     rr = slice(None) if rows is None else list(rows)
     np.testing.assert_allclose(sc_gpu[:, rr], sc_ref[:, rr], rtol=score_rtol, atol=1e-6)
     agree = check_mask_against_oracle(m_gpu, m_ref, sc_ref, w.cu_seqlens, w.block_size, w.causal, w.mode, param, rows)

@@ -170,6 +170,12 @@ def test_error_paths(ctx):
         ctx.build_mask(p, api.Select(threshold=1.5), q, k)
     assert e.value.code == 3
     with pytest.raises(api.UnisparseError) as e:
+        ctx.build_mask(p, api.Select(pool=2), q, k)              # stochastic pooling without its uniform numbers
+    assert e.value.code == 1
+    with pytest.raises(api.UnisparseError) as e:
+        ctx.build_mask(p, api.Select(pool=3), q, k)
+    assert e.value.code == 3
+    with pytest.raises(api.UnisparseError) as e:
         ctx.build_mask(p, api.Select(), q, k, workspace=torch.empty(1024, dtype=torch.uint8, device="cuda"))
     assert e.value.code == 5
 
@@ -270,6 +276,31 @@ def test_max_pooling_option(ctx, oracle, lengths):
     w = W.random_small(H=4, Hkv=2, lengths=lengths, S=128, causal=True, mode=W.TOP_P, param=0.85, seed=18)
     w.pool = 1
     PU.full_pipeline_check(ctx, oracle, w, check_dense=False)
+
+
+@pytest.mark.parametrize("lengths,S,cq,ck,layout", [((256, 384), 128, 8, 8, "htd"), ((133, 37, 300), 128, 16, 4, "thd"),
+                                                     ((192, 70), 64, 2, 16, "htd"), ((512,), 128, 32, 32, "htd")])
+def test_stochastic_pooling_option(ctx, oracle, lengths, S, cq, ck, layout):
+    """Stochastic pooling of the compression-strategy ablation: the token drawn in every window equals the oracle's
+    bit for bit (same uniform numbers, same fp32 inversion), whole and clipped windows, then the usual pipeline."""
+    w = W.random_small(H=4, Hkv=2, lengths=lengths, S=S, causal=True, mode=W.TOP_P, param=0.85, seed=23)
+    w.c_q, w.c_k = cq, ck
+    w.draw_pool_uniforms()
+    PU.full_pipeline_check(ctx, oracle, w, layout=layout, check_dense=False)
+    # key side alone (its own uniform numbers), and magnitudes spread over four orders so the draw is far from uniform
+    rng = np.random.default_rng(5)
+    kf = w.f32()[1] * np.exp(rng.uniform(-4.0, 4.0, size=(w.n_heads_kv, w.total_tokens, 1))).astype(np.float32)
+    kb = W.f32_to_bf16_bits(kf)
+    kf = W.bf16_bits_to_f32(kb)
+    p = PU.problem_of(w)
+    kt = ctx.pool_seq_varlen(p, api.bits_to_device(kb), ck, "htd", 2, torch.from_numpy(w.rand_k).cuda())
+    torch.cuda.synchronize()
+    kt_bits = kt.view(torch.int16).cpu().numpy().view(np.uint16)
+    off = oracle.composite_offsets(w.cu_seqlens, ck)
+    for h in range(w.n_heads_kv):
+        ref = np.concatenate([oracle.stochpool_seq(kf[h, w.cu_seqlens[b]:w.cu_seqlens[b + 1]], ck,
+                                                   w.rand_k[h, off[b]:off[b + 1]]) for b in range(len(lengths))])
+        assert np.array_equal(kt_bits[h], W.f32_to_bf16_bits(ref))
 
 
 def test_one_call_entry_point_equals_two_calls(ctx, oracle):
