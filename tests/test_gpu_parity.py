@@ -342,3 +342,36 @@ def test_strided_views(ctx, oracle):
     torch.cuda.synchronize()
     assert torch.equal(m1, m2) and torch.equal(sc1, sc2)
     assert torch.equal(o1, o2.contiguous()) and torch.equal(l1, l2) and torch.equal(d1, d2.contiguous())
+
+
+def test_randomised_small_problems(ctx, oracle):
+    """Sixty seeded draws over everything a call can vary -- block size, both compression factors, head counts and
+    head compression, 1-3 packed sequences of arbitrary lengths, causal or not, Top-P or budget, pooling strategy,
+    memory layout -- each through the whole pipeline check."""
+    for it in range(60):
+        rng = np.random.default_rng(4000 + it)
+        S = int(rng.choice([64, 128]))
+        cs = [c for c in (1, 2, 4, 8, 16, 32) if S // c in (4, 8, 16, 32, 64)]
+        cq, ck = int(rng.choice(cs)), int(rng.choice(cs))
+        Hkv, G = int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 4]))
+        H = Hkv * G
+        ch = int(rng.choice([c for c in (1, 2, 4, 8) if H % c == 0 and (G % c == 0 or c % G == 0)]))
+        nseq = int(rng.integers(1, 4))
+        lengths = tuple(int(x) for x in rng.integers(1, int(rng.choice([300, 900])), nseq))
+        if rng.random() < 0.3:
+            lengths = tuple(int(S * rng.integers(1, 6)) for _ in range(nseq))
+        causal = bool(rng.random() < 0.7)
+        mode = W.TOP_P if rng.random() < 0.6 else W.TOP_K
+        param = float(rng.choice([0.5, 0.8, 0.9, 0.95, 1.0] if mode == W.TOP_P else [0.1, 0.25, 0.5, 1.0]))
+        pool = int(rng.choice([0, 0, 1, 2]))
+        layout = str(rng.choice(["htd", "thd"]))
+        w = W.random_small(H=H, Hkv=Hkv, lengths=lengths, S=S, causal=causal, mode=mode, param=param, seed=900 + it,
+                           scale=float(rng.choice([0.5, 1.0, 1.5])))
+        w.c_q, w.c_k, w.c_h, w.pool = cq, ck, ch, pool
+        if pool == 2:
+            w.draw_pool_uniforms()
+        try:
+            PU.full_pipeline_check(ctx, oracle, w, layout=layout)
+        except AssertionError as e:
+            raise AssertionError(f"draw {it}: S={S} c=({cq},{ck},{ch}) H={H}/{Hkv} lengths={lengths} causal={causal} "
+                                 f"mode={mode} param={param} pool={pool} {layout}: {e}") from e
