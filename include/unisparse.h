@@ -16,7 +16,9 @@
  * - All tensor pointers are DEVICE pointers unless a comment says HOST.  The caller owns
  *   every buffer (inputs, outputs, workspace).  The library allocates no device memory,
  *   never synchronises the device or a stream, and enqueues work only on the stream given.
- * - Element type of Q, K, V, O and of the composite tokens is bf16 (2 bytes).  head_dim = 128.
+ * - Element type of Q, K, V, O and of the composite tokens is bf16 (2 bytes).  head_dim d = 64, 128 or 256
+ *   (128 is the dimension of every model the paper measures and the one the fast attention kernel is written
+ *   for; 64 and 256 run a plainer kernel).
  * - A problem is a packed batch of B sequences ("varlen"): tokens of all sequences are
  *   concatenated along the token axis, sequence b owning tokens [cu_seqlens[b], cu_seqlens[b+1]).
  *   Sequences never interact.  A length that is not a multiple of block_size gives a shorter last block
@@ -45,7 +47,7 @@ extern "C" {
 #endif
 
 #define UNISPARSE_MAX_SEQS 16      /* sequences per packed batch */
-#define UNISPARSE_HEAD_DIM 128
+#define UNISPARSE_HEAD_DIM 128       /* the default head dimension (and that of unisparse_avgpool_seq) */
 #define UNISPARSE_MAX_BLOCKS_PER_SEQ 4096   /* NK limit (selection sorts one row in LDS) */
 
 typedef struct unisparse_ctx unisparse_ctx;   /* opaque; caches device properties only */
@@ -67,7 +69,7 @@ typedef struct {
     const int32_t *cu_seqlens;       /* HOST */
     int32_t n_heads_q;               /* H */
     int32_t n_heads_kv;              /* H_kv, divides H */
-    int32_t head_dim;                /* must be 128 */
+    int32_t head_dim;                /* d: 64, 128 or 256 */
     int32_t block_size;              /* S: 64 or 128 */
     int32_t causal;                  /* 0 / 1 */
     float softmax_scale;             /* 0 -> 1 / sqrt(head_dim) */
@@ -140,10 +142,10 @@ unisparse_status unisparse_avgpool_seq(unisparse_ctx *ctx, unisparse_tensor x, i
  * token order), so equal inputs and equal random numbers give equal choices everywhere; c <= 32.
  * This is what build_mask applies internally.  Only num_seqs and cu_seqlens of the problem are used for
  * the geometry.
- *   x    : [total_tokens, n_heads, 128] view
+ *   x    : [total_tokens, n_heads, d] view (d = head_dim of the problem)
  *   rand : DEVICE float [n_heads][sum_b ceil(L_b / c)] in [0, 1); read only for UNISPARSE_POOL_STOCHASTIC
  *          (NULL otherwise); UNISPARSE_ERR_NULL if missing
- *   out  : DEVICE bf16 [n_heads][sum_b ceil(L_b / c)][128], contiguous
+ *   out  : DEVICE bf16 [n_heads][sum_b ceil(L_b / c)][d], contiguous
  */
 unisparse_status unisparse_pool_seq_varlen(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor x,
                                            int32_t n_heads, int32_t c, int32_t pool, const float *rand, void *out,
@@ -151,7 +153,7 @@ unisparse_status unisparse_pool_seq_varlen(unisparse_ctx *ctx, const unisparse_p
 
 /*
  * Alg. 1 steps 1-4: composite tokens, compressed softmax scores, block aggregation, selection.
- *   Q : [T, H, 128] view, K : [T, H_kv, 128] view
+ *   Q : [T, H, d] view, K : [T, H_kv, d] view
  *   workspace : DEVICE scratch of at least unisparse_workspace_bytes() bytes, 256-byte aligned
  *   M     : out, uint64 [H][NQ][W]
  *   score : out, optional (may be NULL), float [H / c_h][NQ][NK]; Score(i, j) of Eq. (3) for valid j,
@@ -174,7 +176,7 @@ unisparse_status unisparse_select_blocks(unisparse_ctx *ctx, const unisparse_pro
 /*
  * Alg. 1 step 5 / Sec. 2.2: O = softmax(Q K^T * scale + M~) V over the selected blocks only, with
  * token-level causality inside the diagonal block.
- *   Q, O : [T, H, 128] views;  K, V : [T, H_kv, 128] views;  M as above
+ *   Q, O : [T, H, d] views;  K, V : [T, H_kv, d] views;  M as above
  *   lse  : optional (may be NULL), float [H][T]: natural-log sum of exponentials of the visible logits
  * A query row whose mask row is empty gets O = 0 and lse = -inf.
  */

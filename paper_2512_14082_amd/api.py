@@ -233,7 +233,7 @@ class Context:
                         rand: Optional[torch.Tensor] = None) -> torch.Tensor:
         H = x.shape[1] if layout == "thd" else x.shape[0]
         n_out = sum(-(-(int(p.cu_seqlens[b + 1]) - int(p.cu_seqlens[b])) // c) for b in range(len(p.cu_seqlens) - 1))
-        out = torch.empty((H, n_out, HEAD_DIM), dtype=torch.bfloat16, device=x.device)
+        out = torch.empty((H, n_out, p.head_dim), dtype=torch.bfloat16, device=x.device)
         _check(self.lib.unisparse_pool_seq_varlen(self.handle, p.c, _view(x, layout), H, c, pool, _rand_ptr(rand),
                                                   out.data_ptr(), _stream()))
         return out

@@ -582,6 +582,7 @@ static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
 
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream)
 {
+    if (a.head_dim != kHeadDim) return launch_attention_generic(a, stream);
     const bool dense = a.mask == nullptr;
 #define US_AT(SS, CA, DE) \
     if (a.S == SS && (a.causal != 0) == CA && dense == DE) return attn_launch_t<SS, CA, DE>(a, stream)

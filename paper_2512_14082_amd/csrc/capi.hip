@@ -28,7 +28,7 @@ unisparse_status check_problem(const unisparse_problem *p, Geom *g)
 {
     if (p == nullptr || p->cu_seqlens == nullptr) return UNISPARSE_ERR_NULL;
     if (p->num_seqs < 1 || p->num_seqs > UNISPARSE_MAX_SEQS) return UNISPARSE_ERR_SHAPE;
-    if (p->head_dim != UNISPARSE_HEAD_DIM) return UNISPARSE_ERR_UNSUPPORTED;
+    if (p->head_dim != 64 && p->head_dim != 128 && p->head_dim != 256) return UNISPARSE_ERR_UNSUPPORTED;
     if (p->block_size != 64 && p->block_size != 128) return UNISPARSE_ERR_UNSUPPORTED;
     if (p->n_heads_q < 1 || p->n_heads_kv < 1 || p->n_heads_q % p->n_heads_kv != 0) return UNISPARSE_ERR_SHAPE;
     if (!(p->softmax_scale >= 0.0f) || std::isinf(p->softmax_scale)) return UNISPARSE_ERR_PARAM;
@@ -88,11 +88,11 @@ unisparse_status check_select(const unisparse_problem *p, const unisparse_select
     return UNISPARSE_OK;
 }
 
-unisparse_status check_tensor(const unisparse_tensor &t)
+unisparse_status check_tensor(const unisparse_tensor &t, int head_dim)
 {
     if (t.ptr == nullptr) return UNISPARSE_ERR_NULL;
     if (((uintptr_t)t.ptr & 15) != 0 || t.stride_tok % 8 != 0 || t.stride_head % 8 != 0) return UNISPARSE_ERR_SHAPE;
-    if (t.stride_tok < UNISPARSE_HEAD_DIM && t.stride_head < UNISPARSE_HEAD_DIM) return UNISPARSE_ERR_SHAPE;
+    if (t.stride_tok < head_dim && t.stride_head < head_dim) return UNISPARSE_ERR_SHAPE;
     return UNISPARSE_OK;
 }
 
@@ -132,7 +132,7 @@ WsLayout carve(const unisparse_problem *p, const unisparse_select *s, const Geom
 {
     WsLayout w;
     size_t off = 0;
-    const size_t row = (size_t)UNISPARSE_HEAD_DIM * 2;
+    const size_t row = (size_t)p->head_dim * 2;
     bool whole;
     const size_t Tq = (size_t)composite_offsets(g.st, s->c_q, nullptr, &whole);
     const size_t Tk = (size_t)composite_offsets(g.st, s->c_k, nullptr, &whole);
@@ -169,10 +169,10 @@ unisparse_status attn_impl(const unisparse_problem *p, const Geom &g, unisparse_
                            hipStream_t stream)
 {
     unisparse_status st;
-    if ((st = check_tensor(Q)) != UNISPARSE_OK) return st;
-    if ((st = check_tensor(K)) != UNISPARSE_OK) return st;
-    if ((st = check_tensor(V)) != UNISPARSE_OK) return st;
-    if ((st = check_tensor(O)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(Q, p->head_dim)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(K, p->head_dim)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(V, p->head_dim)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(O, p->head_dim)) != UNISPARSE_OK) return st;
     AttnArgs a;
     a.q = view(Q);
     a.k = view(K);
@@ -186,6 +186,7 @@ unisparse_status attn_impl(const unisparse_problem *p, const Geom &g, unisparse_
     a.n_heads_q = p->n_heads_q;
     a.n_heads_kv = p->n_heads_kv;
     a.S = p->block_size;
+    a.head_dim = p->head_dim;
     a.causal = p->causal;
     a.NQ = g.NQ;
     a.W = g.W;
@@ -262,11 +263,12 @@ unisparse_status unisparse_avgpool_seq(unisparse_ctx *ctx, unisparse_tensor x, i
                                        int32_t c, void *out, void *stream)
 {
     if (ctx == nullptr || out == nullptr) return UNISPARSE_ERR_NULL;
-    unisparse_status st = check_tensor(x);
+    unisparse_status st = check_tensor(x, UNISPARSE_HEAD_DIM);
     if (st != UNISPARSE_OK) return st;
     if (n_heads < 1 || total_tokens < 0 || c < 1 || total_tokens % c != 0) return UNISPARSE_ERR_SHAPE;
     if (((uintptr_t)out & 15) != 0) return UNISPARSE_ERR_SHAPE;
-    hipError_t e = launch_avgpool_seq(view(x), n_heads, total_tokens, c, UNISPARSE_POOL_AVG, reinterpret_cast<bf16_t *>(out),
+    hipError_t e = launch_avgpool_seq(view(x), n_heads, total_tokens, c, UNISPARSE_POOL_AVG, UNISPARSE_HEAD_DIM,
+                                      reinterpret_cast<bf16_t *>(out),
                                       (hipStream_t)stream);
     return e == hipSuccess ? UNISPARSE_OK : UNISPARSE_ERR_HIP;
 }
@@ -279,16 +281,16 @@ unisparse_status unisparse_pool_seq_varlen(unisparse_ctx *ctx, const unisparse_p
     Geom g;
     unisparse_status st;
     if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
-    if ((st = check_tensor(x)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(x, p->head_dim)) != UNISPARSE_OK) return st;
     if (n_heads < 1 || c < 1) return UNISPARSE_ERR_SHAPE;
     if (pool < UNISPARSE_POOL_AVG || pool > UNISPARSE_POOL_STOCHASTIC) return UNISPARSE_ERR_PARAM;
     if (((uintptr_t)out & 15) != 0) return UNISPARSE_ERR_SHAPE;
     if (pool == UNISPARSE_POOL_STOCHASTIC && rand == nullptr) return UNISPARSE_ERR_NULL;
     if (pool == UNISPARSE_POOL_STOCHASTIC && c > 32) return UNISPARSE_ERR_UNSUPPORTED;
     hipError_t e = pool == UNISPARSE_POOL_STOCHASTIC
-                       ? launch_stochpool_seq_varlen(view(x), n_heads, g.st, c, rand, reinterpret_cast<bf16_t *>(out),
+                       ? launch_stochpool_seq_varlen(view(x), n_heads, g.st, c, p->head_dim, rand, reinterpret_cast<bf16_t *>(out),
                                                      (hipStream_t)stream)
-                       : launch_avgpool_seq_varlen(view(x), n_heads, g.st, c, pool, reinterpret_cast<bf16_t *>(out),
+                       : launch_avgpool_seq_varlen(view(x), n_heads, g.st, c, pool, p->head_dim, reinterpret_cast<bf16_t *>(out),
                                                    (hipStream_t)stream);
     return e == hipSuccess ? UNISPARSE_OK : UNISPARSE_ERR_HIP;
 }
@@ -303,8 +305,8 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     unisparse_status st;
     if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
     if ((st = check_select(p, s, &hg)) != UNISPARSE_OK) return st;
-    if ((st = check_tensor(Q)) != UNISPARSE_OK) return st;
-    if ((st = check_tensor(K)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(Q, p->head_dim)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(K, p->head_dim)) != UNISPARSE_OK) return st;
     const WsLayout w = carve(p, s, g, hg, score == nullptr);
     unsigned char *base = reinterpret_cast<unsigned char *>(align256((size_t)(uintptr_t)workspace));
     const size_t lead = (size_t)(base - reinterpret_cast<unsigned char *>(workspace));
@@ -320,22 +322,23 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     const int64_t Tk = composite_offsets(g.st, s->c_k, pa.cu_ck, &whole_k);
     // windows never straddle sequences; with whole windows everywhere the packed batch pools as one flat array
     const bool stoch = s->pool == UNISPARSE_POOL_STOCHASTIC;
-    hipError_t pe = stoch     ? launch_stochpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, s->rand_q, qt, stream)
-                    : whole_q ? launch_avgpool_seq(view(Q), p->n_heads_q, g.T, s->c_q, s->pool, qt, stream)
-                              : launch_avgpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, s->pool, qt, stream);
+    const int d = p->head_dim;
+    hipError_t pe = stoch     ? launch_stochpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, d, s->rand_q, qt, stream)
+                    : whole_q ? launch_avgpool_seq(view(Q), p->n_heads_q, g.T, s->c_q, s->pool, d, qt, stream)
+                              : launch_avgpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, s->pool, d, qt, stream);
     if (pe != hipSuccess) return UNISPARSE_ERR_HIP;
-    pe = stoch     ? launch_stochpool_seq_varlen(view(K), p->n_heads_kv, g.st, s->c_k, s->rand_k, kt, stream)
-         : whole_k ? launch_avgpool_seq(view(K), p->n_heads_kv, g.T, s->c_k, s->pool, kt, stream)
-                   : launch_avgpool_seq_varlen(view(K), p->n_heads_kv, g.st, s->c_k, s->pool, kt, stream);
+    pe = stoch     ? launch_stochpool_seq_varlen(view(K), p->n_heads_kv, g.st, s->c_k, d, s->rand_k, kt, stream)
+         : whole_k ? launch_avgpool_seq(view(K), p->n_heads_kv, g.T, s->c_k, s->pool, d, kt, stream)
+                   : launch_avgpool_seq_varlen(view(K), p->n_heads_kv, g.st, s->c_k, s->pool, d, kt, stream);
     if (pe != hipSuccess) return UNISPARSE_ERR_HIP;
     if (s->c_h > 1) {
         bf16_t *qth = reinterpret_cast<bf16_t *>(base + w.qth);
-        if (launch_avgpool_head(qt, p->n_heads_q, Tq, s->c_h, qth, stream) != hipSuccess)
+        if (launch_avgpool_head(qt, p->n_heads_q, Tq, s->c_h, d, qth, stream) != hipSuccess)
             return UNISPARSE_ERR_HIP;
         qt = qth;
         if (hg.kpool > 1) {
             bf16_t *kth = reinterpret_cast<bf16_t *>(base + w.kth);
-            if (launch_avgpool_head(kt, p->n_heads_kv, Tk, hg.kpool, kth, stream) != hipSuccess)
+            if (launch_avgpool_head(kt, p->n_heads_kv, Tk, hg.kpool, d, kth, stream) != hipSuccess)
                 return UNISPARSE_ERR_HIP;
             kt = kth;
         }
@@ -348,6 +351,7 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     pa.n_heads_q = hg.Hc;
     pa.n_heads_kv = hg.Hkc;
     pa.S = p->block_size;
+    pa.head_dim = p->head_dim;
     pa.c_q = s->c_q;
     pa.c_k = s->c_k;
     pa.causal = p->causal;
@@ -379,7 +383,7 @@ unisparse_status unisparse_sparse_attn(unisparse_ctx *ctx, const unisparse_probl
     Geom g;
     unisparse_status st;
     if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
-    if (g.T == 0) return check_tensor(Q);
+    if (g.T == 0) return check_tensor(Q, p->head_dim);
     return attn_impl(p, g, Q, K, V, M, O, lse, (hipStream_t)stream);
 }
 
@@ -391,7 +395,7 @@ unisparse_status unisparse_full_attn(unisparse_ctx *ctx, const unisparse_problem
     Geom g;
     unisparse_status st;
     if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
-    if (g.T == 0) return check_tensor(Q);
+    if (g.T == 0) return check_tensor(Q, p->head_dim);
     return attn_impl(p, g, Q, K, V, nullptr, O, lse, (hipStream_t)stream);
 }
 
@@ -400,8 +404,8 @@ unisparse_status unisparse_attn(unisparse_ctx *ctx, const unisparse_problem *p, 
                                 size_t workspace_bytes, uint64_t *M, unisparse_tensor O, float *lse, void *stream)
 {
     unisparse_status st;
-    if ((st = check_tensor(V)) != UNISPARSE_OK) return st;
-    if ((st = check_tensor(O)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(V, p->head_dim)) != UNISPARSE_OK) return st;
+    if ((st = check_tensor(O, p->head_dim)) != UNISPARSE_OK) return st;
     st = unisparse_build_mask(ctx, p, s, Q, K, workspace, workspace_bytes, M, nullptr, stream);
     if (st != UNISPARSE_OK) return st;
     return unisparse_sparse_attn(ctx, p, Q, K, V, M, O, lse, stream);

@@ -21,7 +21,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kHeadDim = UNISPARSE_HEAD_DIM;
+constexpr int kHeadDim = 128;           // the head dimension the pipelined attention kernel is written for
 constexpr int kMaxSeqs = UNISPARSE_MAX_SEQS;
 constexpr int kNumXcd = 8;              // MI355X: 8 accelerator dies, workgroups are dealt round-robin to them
 constexpr float kLog2e = 1.4426950408889634f;
@@ -96,19 +96,20 @@ struct Launch {
 };
 
 // ---- kernel launchers (defined one per .hip file) ------------------------------------------
-hipError_t launch_avgpool_seq(const TensorView &x, int n_heads, int64_t total_tokens, int c, int pool, bf16_t *out,
-                              hipStream_t stream);
+// head_dim is 64, 128 or 256 everywhere.
+hipError_t launch_avgpool_seq(const TensorView &x, int n_heads, int64_t total_tokens, int c, int pool, int head_dim,
+                              bf16_t *out, hipStream_t stream);
 // The same per sequence: sequence b owns ceil(L_b / c) composite tokens, its last window may be partial.
 hipError_t launch_avgpool_seq_varlen(const TensorView &x, int n_heads, const SeqTable &st, int c, int pool,
-                                     bf16_t *out, hipStream_t stream);
-hipError_t launch_stochpool_seq_varlen(const TensorView &x, int n_heads, const SeqTable &st, int c, const float *u,
-                                       bf16_t *out, hipStream_t stream);
-hipError_t launch_avgpool_head(const bf16_t *x, int n_heads_in, int64_t tokens, int c_h, bf16_t *out,
+                                     int head_dim, bf16_t *out, hipStream_t stream);
+hipError_t launch_stochpool_seq_varlen(const TensorView &x, int n_heads, const SeqTable &st, int c, int head_dim,
+                                       const float *u, bf16_t *out, hipStream_t stream);
+hipError_t launch_avgpool_head(const bf16_t *x, int n_heads_in, int64_t tokens, int c_h, int head_dim, bf16_t *out,
                                hipStream_t stream);
 
 struct ProxyArgs {
-    const bf16_t *qt;        // [Hc][Tq][128] composite queries (Tq = cu_cq[num_seqs])
-    const bf16_t *kt;        // [Hkc][Tk][128] composite keys
+    const bf16_t *qt;        // [Hc][Tq][d] composite queries (Tq = cu_cq[num_seqs])
+    const bf16_t *kt;        // [Hkc][Tk][d] composite keys
     float *score;            // [Hc][NQ][NK]
     SeqTable st;
     int32_t cu_cq[kMaxSeqs + 1];     // packed offsets of the composite queries / keys: sequence b owns
@@ -117,6 +118,7 @@ struct ProxyArgs {
     int32_t S, c_q, c_k;
     int32_t causal;
     int32_t NQ, NK;
+    int32_t head_dim;        // d
     float scale_log2;        // softmax scale * log2(e)
 };
 hipError_t launch_proxy_scores(const ProxyArgs &a, hipStream_t stream);
@@ -142,9 +144,12 @@ struct AttnArgs {
     SeqTable st;
     int32_t n_heads_q, n_heads_kv;
     int32_t S, causal, NQ, W;
+    int32_t head_dim;
     int64_t total_tokens;
     float scale_log2;
 };
+// head_dim 128: the software-pipelined kernel of attention.hip; 64 and 256: the plain kernel of attention_generic.hip
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream);
+hipError_t launch_attention_generic(const AttnArgs &a, hipStream_t stream);
 
 }  // namespace us

@@ -1,0 +1,11 @@
+// Compressed-space score kernel (proxy_kernel.h) at head dimension 256.
+#include "proxy_kernel.h"
+
+namespace us {
+
+hipError_t proxy_dispatch_d256(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream)
+{
+    return proxy_dispatch_t<256>(a, g, grid, stream);
+}
+
+}  // namespace us

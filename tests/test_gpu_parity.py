@@ -375,3 +375,51 @@ def test_randomised_small_problems(ctx, oracle):
         except AssertionError as e:
             raise AssertionError(f"draw {it}: S={S} c=({cq},{ck},{ch}) H={H}/{Hkv} lengths={lengths} causal={causal} "
                                  f"mode={mode} param={param} pool={pool} {layout}: {e}") from e
+
+
+@pytest.mark.parametrize("d", [64, 256])
+@pytest.mark.parametrize("S,lengths,cq,ck,ch,causal,mode,param,pool,layout", [
+    (128, (512, 384), 8, 8, 1, True, W.TOP_P, 0.9, 0, "htd"),
+    (128, (300, 77, 1000), 16, 4, 2, True, W.TOP_K, 0.3, 0, "thd"),
+    (64, (448,), 4, 4, 1, False, W.TOP_P, 0.8, 1, "htd"),
+    (64, (130, 257), 2, 16, 4, True, W.TOP_P, 0.95, 2, "thd"),
+    (128, (640,), 32, 2, 1, False, W.TOP_K, 0.5, 0, "htd"),
+])
+def test_other_head_dims(ctx, oracle, d, S, lengths, cq, ck, ch, causal, mode, param, pool, layout):
+    """Head dimensions 64 and 256: every stage against the oracle (whole and ragged sequences, every pooling strategy,
+    head compression, both layouts), sparse and dense attention."""
+    w = W.random_small(H=4, Hkv=2, lengths=lengths, S=S, causal=causal, mode=mode, param=param, seed=29, d=d)
+    w.c_q, w.c_k, w.c_h, w.pool = cq, ck, ch, pool
+    if pool == 2:
+        w.draw_pool_uniforms()
+    PU.full_pipeline_check(ctx, oracle, w, layout=layout)
+
+
+def test_other_head_dims_randomised(ctx, oracle):
+    """Forty seeded random small problems at head dimensions 64 and 256 (same draws as the test above for 128)."""
+    for it in range(40):
+        rng = np.random.default_rng(7000 + it)
+        d = int(rng.choice([64, 256]))
+        S = int(rng.choice([64, 128]))
+        cs = [c for c in (1, 2, 4, 8, 16, 32) if S // c in (4, 8, 16, 32, 64)]
+        cq, ck = int(rng.choice(cs)), int(rng.choice(cs))
+        Hkv, G = int(rng.choice([1, 2])), int(rng.choice([1, 2, 4]))
+        H = Hkv * G
+        ch = int(rng.choice([c for c in (1, 2, 4, 8) if H % c == 0 and (G % c == 0 or c % G == 0)]))
+        nseq = int(rng.integers(1, 4))
+        lengths = tuple(int(x) for x in rng.integers(1, 700, nseq))
+        causal = bool(rng.random() < 0.7)
+        mode = W.TOP_P if rng.random() < 0.6 else W.TOP_K
+        param = float(rng.choice([0.5, 0.8, 0.9, 1.0] if mode == W.TOP_P else [0.1, 0.25, 1.0]))
+        pool = int(rng.choice([0, 0, 1, 2]))
+        layout = str(rng.choice(["htd", "thd"]))
+        w = W.random_small(H=H, Hkv=Hkv, lengths=lengths, S=S, causal=causal, mode=mode, param=param, seed=950 + it,
+                           scale=float(rng.choice([0.5, 1.0])), d=d)
+        w.c_q, w.c_k, w.c_h, w.pool = cq, ck, ch, pool
+        if pool == 2:
+            w.draw_pool_uniforms()
+        try:
+            PU.full_pipeline_check(ctx, oracle, w, layout=layout)
+        except AssertionError as e:
+            raise AssertionError(f"draw {it}: d={d} S={S} c=({cq},{ck},{ch}) H={H}/{Hkv} lengths={lengths} "
+                                 f"causal={causal} mode={mode} param={param} pool={pool} {layout}: {e}") from e
