@@ -423,3 +423,49 @@ def test_other_head_dims_randomised(ctx, oracle):
         except AssertionError as e:
             raise AssertionError(f"draw {it}: d={d} S={S} c=({cq},{ck},{ch}) H={H}/{Hkv} lengths={lengths} "
                                  f"causal={causal} mode={mode} param={param} pool={pool} {layout}: {e}") from e
+
+
+@pytest.mark.parametrize("N,causal", [(5, True), (64, True), (65, False), (200, True), (1024, False), (4096, True)])
+def test_selection_on_crafted_scores(ctx, oracle, N, causal):
+    """unisparse_select_blocks on hand-made score rows where ties, zeros and the position of the cut are under
+    control: heavy ties (scores quantised to a few levels), uniform rows, all-zero rows, one dominant block,
+    a cut that falls exactly on a level boundary; every threshold / budget; bit-exact against the oracle."""
+    S, H = 64, 3
+    rng = np.random.default_rng(N)
+    p = api.Problem([0, N * S], H, 1, S, causal)
+    score = np.zeros((H, N, N), dtype=np.float32)
+    kinds = ["levels", "uniform", "zeros", "dominant", "random", "pow2", "sparse"]
+    for h in range(H):
+        for r in range(N):
+            kind = kinds[(r + h) % len(kinds)]
+            if kind == "levels":
+                row = rng.integers(0, 4, N).astype(np.float32) / 8.0           # exact in fp32/fp64: ties everywhere
+            elif kind == "uniform":
+                row = np.full(N, 0.25, np.float32)
+            elif kind == "zeros":
+                row = np.zeros(N, np.float32)
+            elif kind == "dominant":
+                row = np.full(N, 2.0 ** -20, np.float32)
+                row[rng.integers(0, N)] = 1.0
+            elif kind == "pow2":
+                row = (2.0 ** -rng.integers(0, 12, N)).astype(np.float32)      # sums exact: cuts land on boundaries
+            elif kind == "sparse":
+                row = np.where(rng.random(N) < 0.1, rng.random(N), 0.0).astype(np.float32)
+            else:
+                row = rng.random(N).astype(np.float32) ** 4
+            score[h, r] = row
+    rows = None if N <= 1024 else sorted({0, 1, 63, 64, 65, N - 1, *[int(x) for x in rng.integers(0, N, 40)]})
+    for mode, params in ((W.TOP_P, (0.25, 0.5, 0.75, 0.9, 1.0)), (W.TOP_K, (0.01, 0.25, 0.5, 1.0))):
+        for param in params:
+            s = api.Select(mode=mode, threshold=param if mode == W.TOP_P else 0.9,
+                           budget_frac=param if mode == W.TOP_K else 0.25)
+            sc_dev = torch.from_numpy(score).cuda()
+            m_dev = ctx.select_blocks(p, s, sc_dev)
+            torch.cuda.synchronize()
+            m_gpu = api.unpack_mask(m_dev, p.n_cols)
+            m_ref = oracle.select_mask(score, [0, N * S], S, causal, mode, param, rows)
+            rr = slice(None) if rows is None else rows
+            bad = np.argwhere(m_gpu[:, rr] != m_ref[:, rr])
+            assert len(bad) == 0, f"mode {mode} param {param}: first mismatches (head, row, col) {bad[:5].tolist()}"
+            if causal:                                   # the call also clears the scores outside the valid set
+                assert not np.triu(sc_dev.cpu().numpy(), 1).any()
