@@ -49,3 +49,20 @@ def test_status_strings_and_size_queries_without_gpu():
     assert lib.unisparse_mask_words(ragged.c) == 8 * 4 * 1
     bad = api.Problem([0, 100], 8, 3, 128, True)                  # heads do not divide
     assert lib.unisparse_mask_words(bad.c) == 0
+
+
+def test_head_dimensions_and_pooling_options_in_the_size_queries():
+    lib = api.load_library()
+    s = api.Select(c_h=2)
+    sizes = {}
+    for d in (64, 128, 256):
+        p = api.Problem([0, 1000, 1536], 8, 2, 128, True, head_dim=d)
+        assert lib.unisparse_mask_words(p.c) == 8 * 13 * 1
+        sizes[d] = lib.unisparse_workspace_bytes(p.c, s.c)
+    assert 0 < sizes[64] < sizes[128] < sizes[256]                # composite tokens scale with the head dimension
+    assert lib.unisparse_mask_words(api.Problem([0, 512], 8, 2, 128, True, head_dim=96).c) == 0
+    p = api.Problem([0, 512], 8, 2, 128, True)
+    assert lib.unisparse_workspace_bytes(p.c, api.Select(pool=1).c) > 0
+    assert lib.unisparse_workspace_bytes(p.c, api.Select(pool=2).c) == 0     # stochastic pooling without its uniforms
+    assert lib.unisparse_workspace_bytes(p.c, api.Select(pool=7).c) == 0
+    assert ctypes.sizeof(api._Select) == 56                        # four ints, two doubles, two ints, two pointers
