@@ -558,13 +558,9 @@ template <int S, bool CAUSAL, bool DENSE>
 static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
 {
     using C = AttnCfg<S>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attention_kernel<S, CAUSAL, DENSE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static LdsAttr attr;
+    hipError_t e = attr.set(reinterpret_cast<const void *>(&attention_kernel<S, CAUSAL, DENSE>), C::kLdsBytes);
+    if (e != hipSuccess) return e;
     if (a.n_heads_q == 0 || a.NQ == 0) return hipSuccess;
     const int G = a.n_heads_q / a.n_heads_kv;
     AttnOrder ord;

@@ -37,9 +37,12 @@ __global__ __launch_bounds__((GenCfg<D, S>::NT)) void attention_generic_kernel(A
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, lh = lane >> 5, i16 = lane & 15;
 
-    // longest rows first, heads fastest
-    const int row = a.NQ - 1 - (int)(blockIdx.x / a.n_heads_q);
-    const int head = (int)(blockIdx.x % a.n_heads_q);
+    // Workgroup ids are dealt round-robin to the 8 XCDs: the heads of one row (which share K/V per key head) go to
+    // one XCD and its L2, rows go round the XCDs, longest rows first.
+    const int xcd = (int)blockIdx.x % kNumXcd, idx = (int)blockIdx.x / kNumXcd;
+    const int row = a.NQ - 1 - ((idx / a.n_heads_q) * kNumXcd + xcd);
+    if (row < 0) return;
+    const int head = idx % a.n_heads_q;
     const int kvh = head / (a.n_heads_q / a.n_heads_kv);
     int seq, i, nb;
     locate_row(a.st, S, row, seq, i, nb);
@@ -212,15 +215,11 @@ template <int D, int S, bool CAUSAL, bool DENSE>
 static hipError_t gen_launch_t(const AttnArgs &a, hipStream_t stream)
 {
     using C = GenCfg<D, S>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attention_generic_kernel<D, S, CAUSAL, DENSE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
-    const int64_t nblk = (int64_t)a.n_heads_q * a.NQ;
-    if (nblk == 0) return hipSuccess;
+    static LdsAttr attr;
+    hipError_t e = attr.set(reinterpret_cast<const void *>(&attention_generic_kernel<D, S, CAUSAL, DENSE>), C::kLdsBytes);
+    if (e != hipSuccess) return e;
+    if (a.n_heads_q == 0 || a.NQ == 0) return hipSuccess;
+    const int64_t nblk = (int64_t)a.n_heads_q * ((a.NQ + kNumXcd - 1) / kNumXcd) * kNumXcd;
     hipLaunchKernelGGL((attention_generic_kernel<D, S, CAUSAL, DENSE>), dim3((unsigned)nblk), dim3(C::NT), C::kLdsBytes,
                        stream, a);
     return hipGetLastError();

@@ -91,8 +91,21 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-struct Launch {
-    hipStream_t stream;
+// A kernel that needs more than 64 KB of dynamic LDS must be told so once per device (the attribute belongs to the
+// device's copy of the kernel).  One object per kernel instantiation; racing first calls both set it, harmlessly.
+struct LdsAttr {
+    bool done[32] = {};
+    hipError_t set(const void *kernel, int bytes)
+    {
+        int dev = -1;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 32) return hipErrorInvalidDevice;
+        if (done[dev]) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e == hipSuccess) done[dev] = true;
+        return e;
+    }
 };
 
 // ---- kernel launchers (defined one per .hip file) ------------------------------------------

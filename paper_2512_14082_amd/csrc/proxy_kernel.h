@@ -340,22 +340,14 @@ static hipError_t proxy_launch_t(const ProxyArgs &a, const ProxyGeom &g, dim3 gr
     const int lds_bytes = 2 * PxCfg<D>::kStageBytes;
     hipError_t e;
     if (a.causal) {
-        static bool attr_done = false;
-        if (!attr_done) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&proxy_kernel<D, NQB, NKB, true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        static LdsAttr attr;
+        e = attr.set(reinterpret_cast<const void *>(&proxy_kernel<D, NQB, NKB, true>), lds_bytes);
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL((proxy_kernel<D, NQB, NKB, true>), grid, dim3(kPxThreads), lds_bytes, stream, a, g);
     } else {
-        static bool attr_done = false;
-        if (!attr_done) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&proxy_kernel<D, NQB, NKB, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        static LdsAttr attr;
+        e = attr.set(reinterpret_cast<const void *>(&proxy_kernel<D, NQB, NKB, false>), lds_bytes);
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL((proxy_kernel<D, NQB, NKB, false>), grid, dim3(kPxThreads), lds_bytes, stream, a, g);
     }
     return hipGetLastError();
