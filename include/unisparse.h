@@ -48,7 +48,7 @@ extern "C" {
 
 #define UNISPARSE_MAX_SEQS 16      /* sequences per packed batch */
 #define UNISPARSE_HEAD_DIM 128       /* the default head dimension (and that of unisparse_avgpool_seq) */
-#define UNISPARSE_MAX_BLOCKS_PER_SEQ 4096   /* NK limit (selection sorts one row in LDS) */
+#define UNISPARSE_MAX_BLOCKS_PER_SEQ 4096   /* NK limit (selection keeps one row in a wavefront's registers) */
 
 typedef struct unisparse_ctx unisparse_ctx;   /* opaque; caches device properties only */
 

@@ -469,3 +469,21 @@ def test_selection_on_crafted_scores(ctx, oracle, N, causal):
             assert len(bad) == 0, f"mode {mode} param {param}: first mismatches (head, row, col) {bad[:5].tolist()}"
             if causal:                                   # the call also clears the scores outside the valid set
                 assert not np.triu(sc_dev.cpu().numpy(), 1).any()
+
+
+def test_maximum_sequence_count(ctx, oracle):
+    """Sixteen packed sequences (the limit), some empty, some shorter than a block or a pooling window; one more
+    is refused."""
+    rng = np.random.default_rng(33)
+    lengths = [int(x) for x in rng.integers(1, 400, 16)]
+    lengths[3] = 0
+    lengths[9] = 5
+    lengths[15] = 0
+    w = W.random_small(H=4, Hkv=2, lengths=lengths, S=64, causal=True, mode=W.TOP_P, param=0.9, seed=34)
+    w.c_q, w.c_k = 8, 4
+    PU.full_pipeline_check(ctx, oracle, w, layout="thd")
+    q, k, v = PU.device_tensors(w)
+    too_many = api.Problem([0] + list(np.cumsum([8] * 17)), 4, 2, 64, True)
+    with pytest.raises(api.UnisparseError) as e:
+        ctx.full_attn(too_many, q, k, v)
+    assert e.value.code == 2
