@@ -46,7 +46,7 @@
 extern "C" {
 #endif
 
-#define UNISPARSE_MAX_SEQS 16      /* sequences per packed batch */
+#define UNISPARSE_MAX_SEQS 64      /* sequences per packed batch */
 #define UNISPARSE_HEAD_DIM 128       /* the default head dimension (and that of unisparse_avgpool_seq) */
 #define UNISPARSE_MAX_BLOCKS_PER_SEQ 4096   /* NK limit (selection keeps one row in a wavefront's registers) */
 

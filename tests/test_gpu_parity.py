@@ -472,18 +472,19 @@ def test_selection_on_crafted_scores(ctx, oracle, N, causal):
 
 
 def test_maximum_sequence_count(ctx, oracle):
-    """Sixteen packed sequences (the limit), some empty, some shorter than a block or a pooling window; one more
+    """Sixty-four packed sequences (the limit), some empty, some shorter than a block or a pooling window; one more
     is refused."""
     rng = np.random.default_rng(33)
-    lengths = [int(x) for x in rng.integers(1, 400, 16)]
+    lengths = [int(x) for x in rng.integers(1, 300, 64)]
     lengths[3] = 0
     lengths[9] = 5
-    lengths[15] = 0
+    lengths[40] = 1
+    lengths[63] = 0
     w = W.random_small(H=4, Hkv=2, lengths=lengths, S=64, causal=True, mode=W.TOP_P, param=0.9, seed=34)
     w.c_q, w.c_k = 8, 4
     PU.full_pipeline_check(ctx, oracle, w, layout="thd")
     q, k, v = PU.device_tensors(w)
-    too_many = api.Problem([0] + list(np.cumsum([8] * 17)), 4, 2, 64, True)
+    too_many = api.Problem([0] + list(np.cumsum([8] * 65)), 4, 2, 64, True)
     with pytest.raises(api.UnisparseError) as e:
         ctx.full_attn(too_many, q, k, v)
     assert e.value.code == 2
