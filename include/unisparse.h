@@ -75,8 +75,10 @@ typedef struct {
     float softmax_scale;             /* 0 -> 1 / sqrt(head_dim) */
 } unisparse_problem;
 
-/* A [tokens, heads, head_dim] view with arbitrary token / head strides (in elements); the last
- * dimension is contiguous and 16-byte aligned.  Covers both token-major and head-major storage. */
+/* A [tokens, heads, head_dim] view with token / head strides in elements; the last dimension is contiguous and
+ * 16-byte aligned.  Covers both token-major and head-major storage.  Strides are multiples of 8,
+ * head_dim <= stride_tok <= 2^22, stride_head >= 0 (UNISPARSE_ERR_SHAPE otherwise); that heads and tokens of an
+ * output view do not overlap is the caller's business. */
 typedef struct {
     void *ptr;                       /* DEVICE, bf16 */
     int64_t stride_tok;

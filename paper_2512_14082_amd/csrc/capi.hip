@@ -92,7 +92,9 @@ unisparse_status check_tensor(const unisparse_tensor &t, int head_dim)
 {
     if (t.ptr == nullptr) return UNISPARSE_ERR_NULL;
     if (((uintptr_t)t.ptr & 15) != 0 || t.stride_tok % 8 != 0 || t.stride_head % 8 != 0) return UNISPARSE_ERR_SHAPE;
-    if (t.stride_tok < head_dim && t.stride_head < head_dim) return UNISPARSE_ERR_SHAPE;
+    // a token row may not overlap the next one; the attention kernels address a block's rows with 32-bit byte
+    // offsets, which holds for token strides up to 2^22 elements
+    if (t.stride_tok < head_dim || t.stride_tok > ((int64_t)1 << 22) || t.stride_head < 0) return UNISPARSE_ERR_SHAPE;
     return UNISPARSE_OK;
 }
 

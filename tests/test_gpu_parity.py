@@ -163,6 +163,10 @@ def test_error_paths(ctx):
     with pytest.raises(api.UnisparseError) as e:
         ctx.build_mask(p, api.Select(c_q=3), q, k)
     assert e.value.code == 2
+    overlapping = torch.as_strided(q, q.shape, (q.stride(0), 64, 1))   # token rows 64 elements apart: they overlap
+    with pytest.raises(api.UnisparseError) as e:
+        ctx.full_attn(p, overlapping, k, v)
+    assert e.value.code == 2
     with pytest.raises(api.UnisparseError) as e:
         ctx.build_mask(p, api.Select(c_q=1), q, k)               # S / c = 128: no kernel
     assert e.value.code == 4
