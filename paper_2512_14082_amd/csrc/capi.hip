@@ -302,6 +302,7 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
                                       size_t workspace_bytes, uint64_t *M, float *score, void *stream_)
 {
     if (ctx == nullptr || M == nullptr || workspace == nullptr) return UNISPARSE_ERR_NULL;
+    if (((uintptr_t)M & 7) != 0) return UNISPARSE_ERR_SHAPE;          // mask words are 8-byte loads and stores
     Geom g;
     HeadGeom hg;
     unisparse_status st;
@@ -368,6 +369,7 @@ unisparse_status unisparse_select_blocks(unisparse_ctx *ctx, const unisparse_pro
                                          float *score, uint64_t *M, void *stream)
 {
     if (ctx == nullptr || score == nullptr || M == nullptr) return UNISPARSE_ERR_NULL;
+    if (((uintptr_t)M & 7) != 0) return UNISPARSE_ERR_SHAPE;          // mask words are 8-byte loads and stores
     Geom g;
     HeadGeom hg;
     unisparse_status st;
@@ -382,6 +384,7 @@ unisparse_status unisparse_sparse_attn(unisparse_ctx *ctx, const unisparse_probl
                                        unisparse_tensor O, float *lse, void *stream)
 {
     if (ctx == nullptr || M == nullptr) return UNISPARSE_ERR_NULL;
+    if (((uintptr_t)M & 7) != 0) return UNISPARSE_ERR_SHAPE;          // mask words are 8-byte loads and stores
     Geom g;
     unisparse_status st;
     if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
@@ -406,6 +409,7 @@ unisparse_status unisparse_attn(unisparse_ctx *ctx, const unisparse_problem *p, 
                                 size_t workspace_bytes, uint64_t *M, unisparse_tensor O, float *lse, void *stream)
 {
     unisparse_status st;
+    if (p == nullptr) return UNISPARSE_ERR_NULL;
     if ((st = check_tensor(V, p->head_dim)) != UNISPARSE_OK) return st;
     if ((st = check_tensor(O, p->head_dim)) != UNISPARSE_OK) return st;
     st = unisparse_build_mask(ctx, p, s, Q, K, workspace, workspace_bytes, M, nullptr, stream);

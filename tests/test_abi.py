@@ -66,3 +66,20 @@ def test_head_dimensions_and_pooling_options_in_the_size_queries():
     assert lib.unisparse_workspace_bytes(p.c, api.Select(pool=2).c) == 0     # stochastic pooling without its uniforms
     assert lib.unisparse_workspace_bytes(p.c, api.Select(pool=7).c) == 0
     assert ctypes.sizeof(api._Select) == 56                        # four ints, two doubles, two ints, two pointers
+
+
+def test_null_arguments_are_refused_before_any_device_work():
+    """Every launching entry point returns UNISPARSE_ERR_NULL (1) for a missing context / problem, on the host,
+    without touching a device (so this runs without a GPU)."""
+    lib = api.load_library()
+    t = api._Tensor(None, 128, 128)
+    p = api.Problem([0, 256], 2, 1, 128, True)
+    s = api.Select()
+    assert lib.unisparse_avgpool_seq(None, t, 1, 256, 8, None, None) == 1
+    assert lib.unisparse_pool_seq_varlen(None, p.c, t, 1, 8, 0, None, None, None) == 1
+    assert lib.unisparse_build_mask(None, p.c, s.c, t, t, None, 0, None, None, None) == 1
+    assert lib.unisparse_select_blocks(None, p.c, s.c, None, None, None) == 1
+    assert lib.unisparse_sparse_attn(None, p.c, t, t, t, None, t, None, None) == 1
+    assert lib.unisparse_full_attn(None, p.c, t, t, t, t, None, None) == 1
+    assert lib.unisparse_attn(None, None, s.c, t, t, t, None, 0, None, t, None, None) == 1
+    assert lib.unisparse_attn(None, p.c, s.c, t, t, t, None, 0, None, t, None, None) == 1
