@@ -104,7 +104,10 @@ typedef struct {
                                         "Compression Strategy" ablation: UNISPARSE_POOL_MAX (channel-wise maximum of
                                         the window) or UNISPARSE_POOL_STOCHASTIC (one token of the window, drawn by
                                         its share of the window's L2 norms; see unisparse_pool_seq_varlen) */
-    int32_t reserved;                /* must be 0 */
+    int32_t proxy_tiles;             /* tuning: 32-row MFMA tiles per wavefront of the score kernel.  0 = chosen by the
+                                        library (2, or 1 when the problem yields few workgroups: high compression
+                                        ratios, compressed heads); 1 or 2 force it.  1 exists for head_dim 128 and
+                                        block_size / c_q <= 32 (UNISPARSE_ERR_UNSUPPORTED otherwise) */
     const float *rand_q;             /* UNISPARSE_POOL_STOCHASTIC only (else ignored): DEVICE uniform numbers in [0, 1), */
     const float *rand_k;             /* one per composite token: rand_q [H][sum_b ceil(L_b/c_q)],
                                         rand_k [H_kv][sum_b ceil(L_b/c_k)], laid out like the composite tokens.

@@ -49,7 +49,7 @@ class _Tensor(ctypes.Structure):
 class _Select(ctypes.Structure):
     _fields_ = [("c_q", ctypes.c_int32), ("c_k", ctypes.c_int32), ("c_h", ctypes.c_int32), ("mode", ctypes.c_int32),
                 ("threshold", ctypes.c_double), ("budget_frac", ctypes.c_double), ("pool", ctypes.c_int32),
-                ("reserved", ctypes.c_int32), ("rand_q", ctypes.c_void_p), ("rand_k", ctypes.c_void_p)]
+                ("proxy_tiles", ctypes.c_int32), ("rand_q", ctypes.c_void_p), ("rand_k", ctypes.c_void_p)]
 
 
 _lib = None
@@ -148,11 +148,12 @@ class Select:
     pool: int = 0          # 0 = average pooling (Eq. (1)), 1 = max pooling, 2 = stochastic pooling
     rand_q: Optional[torch.Tensor] = None   # stochastic pooling: float32 device uniforms [H, composite queries]
     rand_k: Optional[torch.Tensor] = None   # and [H_kv, composite keys]
+    proxy_tiles: int = 0   # tuning of the score kernel: 0 = automatic, 1 / 2 = 32-row tiles per wavefront
 
     @property
     def c(self):
         self._c = _Select(self.c_q, self.c_k, self.c_h, self.mode, float(self.threshold), float(self.budget_frac),
-                          self.pool, 0, _rand_ptr(self.rand_q), _rand_ptr(self.rand_k))
+                          self.pool, self.proxy_tiles, _rand_ptr(self.rand_q), _rand_ptr(self.rand_k))
         return ctypes.byref(self._c)
 
 

@@ -69,7 +69,9 @@ unisparse_status check_select(const unisparse_problem *p, const unisparse_select
     auto ok = [](int n) { return n == 4 || n == 8 || n == 16 || n == 32 || n == 64; };
     if (!ok(nq) || !ok(nk)) return UNISPARSE_ERR_UNSUPPORTED;
     if (s->mode != UNISPARSE_TOP_P && s->mode != UNISPARSE_TOP_K) return UNISPARSE_ERR_PARAM;
-    if (s->pool < UNISPARSE_POOL_AVG || s->pool > UNISPARSE_POOL_STOCHASTIC || s->reserved != 0) return UNISPARSE_ERR_PARAM;
+    if (s->pool < UNISPARSE_POOL_AVG || s->pool > UNISPARSE_POOL_STOCHASTIC) return UNISPARSE_ERR_PARAM;
+    if (s->proxy_tiles < 0 || s->proxy_tiles > 2) return UNISPARSE_ERR_PARAM;
+    if (s->proxy_tiles == 1 && (p->head_dim != 128 || nq > 32)) return UNISPARSE_ERR_UNSUPPORTED;
     if (s->pool == UNISPARSE_POOL_STOCHASTIC && (s->rand_q == nullptr || s->rand_k == nullptr)) return UNISPARSE_ERR_NULL;
     if (s->mode == UNISPARSE_TOP_P && !(s->threshold > 0.0 && s->threshold <= 1.0)) return UNISPARSE_ERR_PARAM;
     if (s->mode == UNISPARSE_TOP_K && !(s->budget_frac > 0.0 && s->budget_frac <= 1.0)) return UNISPARSE_ERR_PARAM;
@@ -355,6 +357,7 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     pa.n_heads_kv = hg.Hkc;
     pa.S = p->block_size;
     pa.head_dim = p->head_dim;
+    pa.tiles = s->proxy_tiles;
     pa.c_q = s->c_q;
     pa.c_k = s->c_k;
     pa.causal = p->causal;

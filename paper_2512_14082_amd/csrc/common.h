@@ -132,6 +132,7 @@ struct ProxyArgs {
     int32_t causal;
     int32_t NQ, NK;
     int32_t head_dim;        // d
+    int32_t tiles;           // 32-row tiles per wavefront: 0 = automatic, 1 or 2 forced
     float scale_log2;        // softmax scale * log2(e)
 };
 hipError_t launch_proxy_scores(const ProxyArgs &a, hipStream_t stream);

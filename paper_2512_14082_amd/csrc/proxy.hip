@@ -22,13 +22,21 @@ hipError_t launch_proxy_scores(const ProxyArgs &a, hipStream_t stream)
     g.HG = proxy_pick_hg(G);
     g.RC = 4 / g.HG;
     g.GS = G / g.HG;
-    const int rows_per_tile = kPxRowsPerWave * g.RC;
-    g.n_tiles = 0;
-    for (int b = 0; b < a.st.num_seqs; ++b) {
-        int lq = a.cu_cq[b + 1] - a.cu_cq[b];
-        g.n_tiles += (lq + rows_per_tile - 1) / rows_per_tile;
+    // Workgroups of 4 wavefronts x 64 rows; a problem that yields fewer than four workgroups per CU (few composite
+    // queries: high compression ratios, compressed heads) is cut into wavefronts of 32 rows instead, twice as many
+    // workgroups of half the length, which the causal triangle needs to balance.
+    int64_t nblk = 0;
+    for (g.QT = 2; g.QT >= 1; --g.QT) {
+        const int rows_per_tile = 32 * g.QT * g.RC;
+        g.n_tiles = 0;
+        for (int b = 0; b < a.st.num_seqs; ++b) {
+            int lq = a.cu_cq[b + 1] - a.cu_cq[b];
+            g.n_tiles += (lq + rows_per_tile - 1) / rows_per_tile;
+        }
+        nblk = (int64_t)a.n_heads_kv * g.GS * g.n_tiles;
+        const bool want_one = a.tiles == 1 || (a.tiles == 0 && nblk < 4 * 256);
+        if (!(want_one && g.QT == 2 && proxy_has_single_tile(a.head_dim, a.S / a.c_q))) break;
     }
-    int64_t nblk = (int64_t)a.n_heads_kv * g.GS * g.n_tiles;
     if (nblk == 0) return hipSuccess;
     dim3 grid((unsigned)nblk);
     switch (a.head_dim) {

@@ -17,7 +17,7 @@ namespace us {
 
 constexpr int kPxThreads = 256;
 constexpr int kPxStageKeys = 128;          // composite keys per LDS stage
-constexpr int kPxRowsPerWave = 64;
+constexpr int kPxRowsPerWave = 64;         // query rows per wavefront: two MFMA tiles of 32 (one when QT = 1)
 template <int D>
 struct PxCfg {
     static constexpr int kSteps = D / 16;                  // MFMA steps over the head dimension
@@ -52,14 +52,17 @@ struct ProxyGeom {
     int RC;          // 64-row chunks per head in a workgroup (4 / HG)
     int GS;          // head slices per key head (G / HG)
     int n_tiles;     // query tiles over all sequences
+    int QT;          // 32-row MFMA tiles per wavefront: 2, or 1 to get twice the workgroups out of a small problem
 };
 
-template <int D, int NQB, int NKB, bool CAUSAL>
+template <int D, int NQB, int NKB, bool CAUSAL, int QT = 2>
 __global__ __launch_bounds__(kPxThreads) __attribute__((amdgpu_waves_per_eu(PxCfg<D>::kWaves, PxCfg<D>::kWaves)))
 void proxy_kernel(ProxyArgs a, ProxyGeom g)
 {
     using C = PxCfg<D>;
     constexpr int kPxPitch = C::kPitch, kPxStageBytes = C::kStageBytes, kHeadDim = D;
+    constexpr int kPxRowsPerWave = 32 * QT;                // shadows the two-tile default
+    static_assert(QT == 2 || NQB <= 32, "a query block must stay inside one wavefront");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -115,10 +118,10 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
     const int lim_first = limit_of(w_first), lim_last = limit_of(w_last);
 
     // ---- query rows of this lane as B operands ---------------------------------------------------
-    bf16x8 qreg[2][C::kSteps];
-    int lim_row[2];
+    bf16x8 qreg[QT][C::kSteps];
+    int lim_row[QT];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QT; ++qb) {
         int t = min(t0 + 32 * qb + lr, Lq - 1);
         lim_row[qb] = limit_of(t);
         const bf16_t *src = a.qt + ((int64_t)head * Tq + a.cu_cq[seq] + t) * kHeadDim + 8 * lh;
@@ -145,13 +148,18 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
     };
 
     const float c2 = a.scale_log2;
-    float m_run[2] = {-INFINITY, -INFINITY};
-    float l_run[2] = {0.0f, 0.0f};
-    float mc[2] = {0.0f, 0.0f}, wnorm[2] = {0.0f, 0.0f};
+    float m_run[QT], l_run[QT], mc[QT], wnorm[QT];
+#pragma unroll
+    for (int qb = 0; qb < QT; ++qb) {
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.0f;
+        mc[qb] = 0.0f;
+        wnorm[qb] = 0.0f;
+    }
 
     // ---- per-tile work, as separate pieces so that the MFMAs of one tile can run under the VALU work of another
     // S^T of one 32-key tile for both query tiles (each K operand read feeds two MFMAs)
-    auto mfma_tile = [&](f32x16 (&dst)[2], const unsigned char *kb, int sub) __attribute__((always_inline)) {
+    auto mfma_tile = [&](f32x16 (&dst)[QT], const unsigned char *kb, int sub) __attribute__((always_inline)) {
         f32x16 zero;
 #pragma unroll
         for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
@@ -159,14 +167,15 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
 #pragma unroll
         for (int ks = 0; ks < C::kSteps; ++ks) {
             bf16x8 ka = *reinterpret_cast<const bf16x8 *>(arow + 32 * ks);
-            dst[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[0][ks], ks == 0 ? zero : dst[0], 0, 0, 0);
-            dst[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[1][ks], ks == 0 ? zero : dst[1], 0, 0, 0);
+#pragma unroll
+            for (int qb = 0; qb < QT; ++qb)
+                dst[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][ks], ks == 0 ? zero : dst[qb], 0, 0, 0);
         }
     };
     // first sweep: running maximum and denominator of every composite query row
-    auto stats_tile = [&](const f32x16 (&src)[2]) __attribute__((always_inline)) {
+    auto stats_tile = [&](const f32x16 (&src)[QT]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < QT; ++qb) {
             float mx = src[qb][0];
 #pragma unroll
             for (int v = 1; v < 16; ++v) mx = fmaxf(mx, src[qb][v]);
@@ -183,7 +192,7 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
     };
     // second sweep: normalised probabilities summed over the composite keys of each key block (registers),
     // then over the composite queries of each query block (lanes), stored as Score(i, j)
-    auto bins_tile = [&](const f32x16 (&src)[2], int s_lo, int sub) __attribute__((always_inline)) {
+    auto bins_tile = [&](const f32x16 (&src)[QT], int s_lo, int sub) __attribute__((always_inline)) {
         // Key blocks against the registers of a 32-key tile: register v of a lane holds key
         // 8 (v / 4) + 4 lh + v % 4.  n_k >= 8: a block is one or more groups of 8 keys, summed
         // over both lane halves; n_k = 4: a block is the four keys of one lane half; n_k = 64: a
@@ -192,9 +201,9 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
         constexpr int NBK = kHalfBlocks ? 4 : (NKB >= 32 ? 1 : 32 / NKB);   // bins per lane
         constexpr int GPB = kHalfBlocks ? 1 : (NKB >= 32 ? 4 : NKB / 8);    // register groups per bin
         constexpr int QR = NQB < 32 ? NQB : 32;                             // lanes of one query block
-        float bin[2][NBK];
+        float bin[QT][NBK];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < QT; ++qb) {
 #pragma unroll
             for (int b = 0; b < NBK; ++b) bin[qb][b] = 0.0f;
 #pragma unroll
@@ -208,13 +217,13 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
                 bin[qb][b] = x;
             }
         }
-        if (NQB == 64) {                       // the wavefront's 64 rows are one query block
+        if constexpr (NQB == 64) {             // the wavefront's 64 rows are one query block
 #pragma unroll
             for (int b = 0; b < NBK; ++b) bin[0][b] += bin[1][b];
         }
         if ((kHalfBlocks || lh == 0) && (lr % QR) == 0) {
 #pragma unroll
-            for (int qb = 0; qb < (NQB == 64 ? 1 : 2); ++qb) {
+            for (int qb = 0; qb < (NQB == 64 ? 1 : QT); ++qb) {
                 int t = t0 + 32 * qb + lr;
                 if (t < Lq) {
                     int i = t / NQB;
@@ -234,10 +243,10 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
     // Software pipeline over the tiles that every row of the wavefront sees in full: the MFMAs of a tile are
     // issued together with the VALU work of the tile before it (two sets of accumulators), across the stage
     // barriers.  sA holds the tile whose VALU work is still pending.
-    f32x16 sA[2], sB[2];
+    f32x16 sA[QT], sB[QT];
     bool pend = false;
     int pend_slo = 0, pend_sub = 0;
-    auto valu_tile = [&](const f32x16 (&src)[2], auto pass_c, int s_lo, int sub) __attribute__((always_inline)) {
+    auto valu_tile = [&](const f32x16 (&src)[QT], auto pass_c, int s_lo, int sub) __attribute__((always_inline)) {
         if constexpr (decltype(pass_c)::value == 0) stats_tile(src);
         else bins_tile(src, s_lo, sub);
     };
@@ -247,10 +256,11 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
 #pragma unroll
         for (int k = 0; k < C::kSteps; ++k) {
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x002, MIXV, 0);   // VALU
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, MIXV, 0);
+#pragma unroll
+            for (int qb = 0; qb < QT; ++qb) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, MIXV, 0);   // VALU
+            }
         }
     };
 
@@ -297,11 +307,11 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
                         const int s_lo = s0 + 32 * sub;
                         if (s_lo > lim_last) break;
                         const bool partial = s_lo + 31 > lim_first;
-                        f32x16 sacc[2];
+                        f32x16 sacc[QT];
                         mfma_tile(sacc, kb, sub);
                         if (partial) {
 #pragma unroll
-                            for (int qb = 0; qb < 2; ++qb)
+                            for (int qb = 0; qb < QT; ++qb)
 #pragma unroll
                                 for (int v = 0; v < 16; ++v) {
                                     int key = s_lo + 8 * (v >> 2) + 4 * lh + (v & 3);
@@ -321,7 +331,7 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
         }
         if constexpr (pass == 0) {
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
+            for (int qb = 0; qb < QT; ++qb) {
                 float m_o = swap_half(m_run[qb]), l_o = swap_half(l_run[qb]);
                 float m_t = fmaxf(m_run[qb], m_o);          // finite: every row sees at least key 0
                 float l_t = l_run[qb] * fast_exp2((m_run[qb] - m_t) * c2) + l_o * fast_exp2((m_o - m_t) * c2);
@@ -334,32 +344,40 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
     });
 }
 
-template <int D, int NQB, int NKB>
+template <int D, int NQB, int NKB, int QT = 2>
 static hipError_t proxy_launch_t(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream)
 {
     const int lds_bytes = 2 * PxCfg<D>::kStageBytes;
     hipError_t e;
     if (a.causal) {
         static LdsAttr attr;
-        e = attr.set(reinterpret_cast<const void *>(&proxy_kernel<D, NQB, NKB, true>), lds_bytes);
+        e = attr.set(reinterpret_cast<const void *>(&proxy_kernel<D, NQB, NKB, true, QT>), lds_bytes);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((proxy_kernel<D, NQB, NKB, true>), grid, dim3(kPxThreads), lds_bytes, stream, a, g);
+        hipLaunchKernelGGL((proxy_kernel<D, NQB, NKB, true, QT>), grid, dim3(kPxThreads), lds_bytes, stream, a, g);
     } else {
         static LdsAttr attr;
-        e = attr.set(reinterpret_cast<const void *>(&proxy_kernel<D, NQB, NKB, false>), lds_bytes);
+        e = attr.set(reinterpret_cast<const void *>(&proxy_kernel<D, NQB, NKB, false, QT>), lds_bytes);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((proxy_kernel<D, NQB, NKB, false>), grid, dim3(kPxThreads), lds_bytes, stream, a, g);
+        hipLaunchKernelGGL((proxy_kernel<D, NQB, NKB, false, QT>), grid, dim3(kPxThreads), lds_bytes, stream, a, g);
     }
     return hipGetLastError();
 }
+
+// The one-tile-per-wavefront variants exist where small grids occur in practice: head dimension 128 and query
+// blocks of at most 32 composite tokens (high compression ratios).
+constexpr bool proxy_has_single_tile(int head_dim, int nqb) { return head_dim == 128 && nqb <= 32; }
 
 // All granularities of one head dimension; each head dimension is compiled in a translation unit of its own.
 template <int D>
 static hipError_t proxy_dispatch_t(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream)
 {
     const int nq = a.S / a.c_q, nk = a.S / a.c_k;
-#define US_PX(NQB, NKB) \
-    if (nq == NQB && nk == NKB) return proxy_launch_t<D, NQB, NKB>(a, g, grid, stream)
+#define US_PX(NQB, NKB)                                                                  \
+    if (nq == NQB && nk == NKB) {                                                        \
+        if constexpr (proxy_has_single_tile(D, NQB))                                     \
+            if (g.QT == 1) return proxy_launch_t<D, NQB, NKB, 1>(a, g, grid, stream);    \
+        return proxy_launch_t<D, NQB, NKB>(a, g, grid, stream);                          \
+    }
     US_PX(4, 4); US_PX(4, 8); US_PX(4, 16); US_PX(4, 32); US_PX(4, 64);
     US_PX(8, 4); US_PX(8, 8); US_PX(8, 16); US_PX(8, 32); US_PX(8, 64);
     US_PX(16, 4); US_PX(16, 8); US_PX(16, 16); US_PX(16, 32); US_PX(16, 64);

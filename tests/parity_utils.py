@@ -121,6 +121,14 @@ def full_pipeline_check(ctx, oracle, w: W.Workload, layout="htd", check_dense=Tr
                                       c_h=w.c_h, rows=rows, pool=w.pool, rand=rand_of(w))
     rr = slice(None) if rows is None else list(rows)
     np.testing.assert_allclose(sc_gpu[:, rr], sc_ref[:, rr], rtol=score_rtol, atol=1e-6)
+    # -- the score kernel's two tilings (one or two 32-row tiles per wavefront) do the same arithmetic per row
+    if w.head_dim == 128 and w.block_size // w.c_q <= 32:
+        for tiles in (1, 2):
+            s_t = select_of(w)
+            s_t.proxy_tiles = tiles
+            m_t, sc_t = ctx.build_mask(p, s_t, q, k, layout, want_score=True)
+            torch.cuda.synchronize()
+            assert torch.equal(sc_t, sc_dev) and torch.equal(m_t, m_dev), f"proxy_tiles={tiles} changes the result"
     agree = check_mask_against_oracle(m_gpu, m_ref, sc_ref, w.cu_seqlens, w.block_size, w.causal, w.mode, param, rows)
     # -- selection alone is index work: on the GPU's own scores it must match the oracle bit for bit
     m_sel = oracle.select_mask(sc_gpu, w.cu_seqlens, w.block_size, w.causal, w.mode, param, rows)
