@@ -34,7 +34,12 @@
  * - Errors: every call validates its arguments on the host before launching anything and
  *   returns a status; on error no kernel is launched and no output is touched.  Launch
  *   failures reported by HIP map to UNISPARSE_ERR_HIP.
- * - stream arguments are hipStream_t values passed as void* (NULL = the null stream).
+ * - stream arguments are hipStream_t values passed as void* (NULL = the null stream).  Work goes to the device
+ *   that is current in the calling thread, which must be the stream's device.
+ * - The first launch of a kernel on a device raises that kernel's dynamic-LDS limit (a host-side HIP call), so a
+ *   stream capture should follow one ordinary call of the same entry point with the same configuration; after
+ *   that the calls are launches only - no allocation, no memset, no synchronisation.
+ * - Calls may come from several host threads; concurrent calls that share an output or workspace buffer race.
  */
 #ifndef UNISPARSE_H
 #define UNISPARSE_H
