@@ -254,6 +254,29 @@ class Context:
                                              ws.data_ptr(), ws.numel(), m.data_ptr(), sp, _stream()))
         return m, score
 
+    def tune(self, p: Problem, s: Select, q: torch.Tensor, k: torch.Tensor, layout: str = "htd", reps: int = 3) -> Select:
+        """Time ``build_mask`` with each tiling of the score kernel this problem admits (``proxy_tiles`` 1 and 2) and
+        set the faster one in ``s`` (the library's own choice, ``proxy_tiles = 0``, is a fixed rule).  Both tilings
+        compute identical masks; only the launch shape differs.  Synchronises the device."""
+        ws, m = self.alloc_workspace(p, s), self.alloc_mask(p)
+        best, best_ms = 0, float("inf")
+        for tiles in (2, 1):
+            if tiles == 1 and (p.head_dim != 128 or p.block_size // s.c_q > 32):
+                continue
+            s.proxy_tiles = tiles
+            self.build_mask(p, s, q, k, layout, workspace=ws, mask=m)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                self.build_mask(p, s, q, k, layout, workspace=ws, mask=m)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            if ms < best_ms:
+                best, best_ms = tiles, ms
+        s.proxy_tiles = best
+        return s
+
     def select_blocks(self, p: Problem, s: Select, score: torch.Tensor, mask: Optional[torch.Tensor] = None):
         m = mask if mask is not None else self.alloc_mask(p)
         _check(self.lib.unisparse_select_blocks(self.handle, p.c, s.c, score.data_ptr(), m.data_ptr(), _stream()))

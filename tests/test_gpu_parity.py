@@ -523,3 +523,15 @@ def test_graph_capture_and_replay(ctx, oracle):
     qf, kf, vf = w.f32()
     o_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, 128, True, api.unpack_mask(m_g, p.n_cols))
     PU.check_output(o_g.float().cpu().numpy(), o_ref, "graph replay")
+
+
+def test_tuning_picks_a_tiling_and_keeps_the_mask(ctx, oracle):
+    w = W.gqa_planted(L=4096, H=4, Hkv=2, S=128, P=0.9, seed=63)
+    q, k, v = PU.device_tensors(w)
+    p, s = PU.problem_of(w), PU.select_of(w)
+    m0, _ = ctx.build_mask(p, s, q, k)
+    ctx.tune(p, s, q, k)
+    assert s.proxy_tiles in (1, 2)
+    m1, _ = ctx.build_mask(p, s, q, k)
+    torch.cuda.synchronize()
+    assert torch.equal(m0, m1)
