@@ -342,9 +342,15 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         sm_sum[par] += sm_x[par][u & 1];
         if constexpr (u + 1 < 16) sm_x[par][(u + 1) & 1] = fast_exp2(sm_a[par][(u + 1) & 1]);
         if constexpr (u + 2 < 16) sm_a[par][u & 1] = fmaf(sacc[par][u + 2], c2, -sm_msc[par]);
-        asm volatile("" : "+v"(w), "+v"(sm_sum[par]), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]), "+v"(sm_a[par][0]),
-                          "+v"(sm_a[par][1]), "+v"(next));
-        if constexpr ((u & 1) != 0) pbw[par][u >> 3][(u >> 1) & 3] = w;
+        // (the packed pair takes part in the pin only where it exists: a pinned constant would cost a move)
+        if constexpr ((u & 1) != 0) {
+            asm volatile("" : "+v"(w), "+v"(sm_sum[par]), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]), "+v"(sm_a[par][0]),
+                              "+v"(sm_a[par][1]), "+v"(next));
+            pbw[par][u >> 3][(u >> 1) & 3] = w;
+        } else {
+            asm volatile("" : "+v"(sm_sum[par]), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]), "+v"(sm_a[par][0]),
+                              "+v"(sm_a[par][1]), "+v"(next));
+        }
     };
     // closes sub-step `par`: row sum, and O^T (which holds the products up to the sub-step before) rescaled
     auto sm_finish = [&](auto par_c) __attribute__((always_inline)) {
