@@ -220,7 +220,7 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     // State is kept twice, indexed by the parity of the sub-step (= t).
     f32x16 sacc[2];                              // S^T tile
     u32x4 pbw[2][2];                             // P^T tile as packed bf16 pairs: two MFMA operands of 16 keys
-    float sm_msc[2], sm_alpha[2], sm_sum[2];     // scaled running maximum, rescale factor, row sum of the tile
+    float sm_msc[2], sm_alpha[2], sm_sum[2];     // scaled reference value of the exponentials, rescale factor, row sum
     float sm_a[2][2], sm_x[2][2];                // exponent arguments / exponentials in flight (even, odd value)
     float sm_ma = -INFINITY, sm_mb = -INFINITY;
 
@@ -274,10 +274,12 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
 
     // ---- online softmax in chunks of a few instructions (lane-local per query row) -----------------------
     // Per sub-step the 16 values of a lane go through
-    //   MX: row maximum, exchange with the other half of the key rows (lane ^ 32), running maximum, rescale
-    //       factor; also starts the pipeline below (arguments of values 0 and 1, exponential of value 0)
-    //   EX: one chunk per value u: [pack values u-1, u to bf16] row sum += exp(u); exp(u+1); argument(u+2)
+    //   MX: row maximum, exchange with the other half of the key rows (lane ^ 32), reference value of the
+    //       exponentials, rescale factor; also starts the pipeline below (arguments of values 0 and 1,
+    //       exponential of value 0)
+    //   EX: one chunk per value u: [pack values u-1, u to bf16]; exp(u+1); argument(u+2)
     //       - nothing in a chunk uses a result of the same chunk, so VALU latency never stalls the wavefront
+    //   and the row sum, taken from the packed values when the sub-step closes.
     // Every chunk is tied (empty asm) to the operand of the MFMA that follows it, which keeps it between the
     // same two MFMAs in the machine code: the matrix pipe hides a handful of VALU instructions per MFMA.
     // Last visited block only: keys after the query's own position (diagonal block of a causal row) and keys
@@ -297,6 +299,9 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     };
     auto needs_mask = [&](int j) __attribute__((always_inline)) -> bool { return (CAUSAL && j == i) || j == j_short; };
     constexpr int NMX = 6;
+    // The two kernels close a sub-step differently (measured: each way is the faster one for its kernel).
+    constexpr bool kLazy = !DENSE;
+    const float lazy_gap = 8.0f / c2;            // 8 binary orders of magnitude, in units of the raw logits
     auto mx_chunk = [&](auto par_c, auto m_c, bf16x8 &next) __attribute__((always_inline)) {
         constexpr int par = decltype(par_c)::value, m = decltype(m_c)::value;
         const f32x16 &s = sacc[par];
@@ -314,7 +319,13 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         } else if constexpr (m == 2) {
             const float mx = fmaxf(sm_ma, sm_mb);
             auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-            sm_ma = fmaxf(fmaxf(m_run, __uint_as_float(sw[0])), __uint_as_float(sw[1]));     // new running maximum
+            // Sparse kernel: the reference value of the exponentials (m_run) follows the row maximum lazily - it
+            // moves only when the tile's maximum exceeds it by more than 2^8 in the exponent, so probabilities stay
+            // <= 256 (exact after the final division by the row sum) and the rescaling of O^T becomes rare.  Dense
+            // kernel: the reference is the running maximum (its long rows rescale seldom anyway).
+            const float tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            if constexpr (kLazy) sm_ma = tmax > m_run + lazy_gap ? tmax : m_run;
+            else sm_ma = fmaxf(m_run, tmax);
             asm volatile("" : "+v"(sm_ma), "+v"(next));
         } else if constexpr (m == 3) {
             const float m_safe = sm_ma == -INFINITY ? 0.0f : sm_ma;
@@ -325,36 +336,64 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         } else if constexpr (m == 4) {
             sm_a[par][0] = fmaf(s[0], c2, -sm_msc[par]);
             sm_a[par][1] = fmaf(s[1], c2, -sm_msc[par]);
-            sm_sum[par] = 0.0f;
-            asm volatile("" : "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(sm_sum[par]), "+v"(next));
+            if constexpr (kLazy) {
+                asm volatile("" : "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
+            } else {
+                sm_sum[par] = 0.0f;
+                asm volatile("" : "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(sm_sum[par]), "+v"(next));
+            }
         } else {
             sm_x[par][0] = fast_exp2(sm_a[par][0]);
             asm volatile("" : "+v"(sm_x[par][0]), "+v"(next));
         }
     };
+    // EX chunk of value u: [pack values u-1, u to bf16]; (dense kernel: row sum += exp(u);) exp(u+1); argument(u+2).
     auto ex_chunk = [&](auto par_c, auto u_c, bf16x8 &next) __attribute__((always_inline)) {
         constexpr int par = decltype(par_c)::value, u = decltype(u_c)::value;
-        uint32_t w = 0;
         if constexpr ((u & 1) != 0) {
             f32x2 pe = {sm_x[par][0], sm_x[par][1]};
-            w = __builtin_bit_cast(uint32_t, __builtin_convertvector(pe, bf16x2));
+            pbw[par][u >> 3][(u >> 1) & 3] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pe, bf16x2));
         }
-        sm_sum[par] += sm_x[par][u & 1];
+        if constexpr (!kLazy) sm_sum[par] += sm_x[par][u & 1];
         if constexpr (u + 1 < 16) sm_x[par][(u + 1) & 1] = fast_exp2(sm_a[par][(u + 1) & 1]);
         if constexpr (u + 2 < 16) sm_a[par][u & 1] = fmaf(sacc[par][u + 2], c2, -sm_msc[par]);
-        // (the packed pair takes part in the pin only where it exists: a pinned constant would cost a move)
-        if constexpr ((u & 1) != 0) {
-            asm volatile("" : "+v"(w), "+v"(sm_sum[par]), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]), "+v"(sm_a[par][0]),
-                              "+v"(sm_a[par][1]), "+v"(next));
-            pbw[par][u >> 3][(u >> 1) & 3] = w;
+        // (only values that exist take part in a pin: a pinned constant would cost a move)
+        if constexpr (kLazy) {
+            if constexpr ((u & 1) != 0) {
+                asm volatile("" : "+v"(pbw[par][u >> 3][(u >> 1) & 3]), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]),
+                                  "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
+            } else {
+                asm volatile("" : "+v"(sm_x[par][0]), "+v"(sm_x[par][1]), "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
+            }
         } else {
-            asm volatile("" : "+v"(sm_sum[par]), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]), "+v"(sm_a[par][0]),
-                              "+v"(sm_a[par][1]), "+v"(next));
+            if constexpr ((u & 1) != 0) {
+                asm volatile("" : "+v"(pbw[par][u >> 3][(u >> 1) & 3]), "+v"(sm_sum[par]), "+v"(sm_x[par][0]),
+                                  "+v"(sm_x[par][1]), "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
+            } else {
+                asm volatile("" : "+v"(sm_sum[par]), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]), "+v"(sm_a[par][0]),
+                                  "+v"(sm_a[par][1]), "+v"(next));
+            }
         }
     };
-    // closes sub-step `par`: row sum, and O^T (which holds the products up to the sub-step before) rescaled
+    // Closes sub-step `par`.  Sparse kernel: the row sum is taken here, in one piece beside the other wavefront's
+    // MFMAs, over the bf16-rounded probabilities just packed - the very values the PV product multiplies, so that
+    // the rounding cancels between numerator and denominator (with a lazy reference the largest probability of a
+    // row is no longer an exact 1; a row dominated by one key still returns that key's V exactly).  Dense kernel:
+    // the sum of the unrounded values was kept along the chain.  O^T (which holds the products up to the sub-step
+    // before) is rescaled when a reference value moved.
     auto sm_finish = [&](auto par_c) __attribute__((always_inline)) {
         constexpr int par = decltype(par_c)::value;
+        if constexpr (kLazy) {
+            float lo[2] = {0.0f, 0.0f}, hi[2] = {0.0f, 0.0f};
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    lo[g] += __uint_as_float(pbw[par][g][e] << 16);
+                    hi[g] += __uint_as_float(pbw[par][g][e] & 0xffff0000u);
+                }
+            sm_sum[par] = (lo[0] + hi[0]) + (lo[1] + hi[1]);
+        }
         l_run = fmaf(l_run, sm_alpha[par], sm_sum[par]);
         if (__any(sm_alpha[par] != 1.0f)) {
 #pragma unroll
@@ -483,7 +522,7 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         }
         static_for<NMX>([&](auto m_c) __attribute__((always_inline)) { mx_chunk(c0, m_c, opnd[0]); });
         static_for<16>([&](auto u_c) __attribute__((always_inline)) { ex_chunk(c0, u_c, opnd[0]); });
-        l_run = sm_sum[0];
+        sm_finish(c0);
         static_for<NMX>([&](auto m_c) __attribute__((always_inline)) { mx_chunk(c1, m_c, opnd[0]); });
         flip_k();                                 // block 1's K is in buffer 1
         __syncthreads();                          // K buffer 0 is reloaded from the first iteration on

@@ -125,33 +125,40 @@ __global__ __launch_bounds__((GenCfg<D, S>::NT)) void attention_generic_kernel(A
 #pragma unroll
             for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sacc[v]);
             mx = fmaxf(mx, swap_half(mx));
-            const float m_new = fmaxf(m_run, mx);
+            // lazy reference: it moves only when the tile's maximum exceeds it by more than 2^8 in the exponent, so
+            // probabilities stay <= 256 and the rescaling of O^T below is rare
+            const float m_new = mx > m_run + 8.0f / c2 ? mx : m_run;
             const float m_safe = m_new == -INFINITY ? 0.0f : m_new;
             const float alpha = fast_exp2((m_run - m_safe) * c2);
             const float msc = m_safe * c2;
-            float p[16], sum = 0.0f;
+            float p[16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                p[v] = fast_exp2(fmaf(sacc[v], c2, -msc));
-                sum += p[v];
-            }
-            l_run = l_run * alpha + sum;
+            for (int v = 0; v < 16; ++v) p[v] = fast_exp2(fmaf(sacc[v], c2, -msc));
             m_run = m_new;
+            if (__any(alpha != 1.0f)) {
 #pragma unroll
-            for (int db = 0; db < C::kDimBlocks; ++db)
+                for (int db = 0; db < C::kDimBlocks; ++db)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+                    for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+            }
             // P^T as B operands: 16-key group g takes registers 8 g .. 8 g + 7 (keys 4 lh + 0..3 and 8 + 4 lh + 0..3
             // of the group); the V^T operand below supplies the same keys in the same slots
+            // The row sum is taken over the rounded probabilities, the values the product below multiplies, so that the
+            // rounding cancels between numerator and denominator.
             bf16x8 pb[2];
+            float sum = 0.0f;
 #pragma unroll
             for (int g = 0; g < 2; ++g) {
                 u32x4 w;
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
+                for (int e = 0; e < 4; ++e) {
                     w[e] = f32_to_bf16_rne(p[8 * g + 2 * e]) | (f32_to_bf16_rne(p[8 * g + 2 * e + 1]) << 16);
+                    sum += __uint_as_float(w[e] << 16);
+                    sum += __uint_as_float(w[e] & 0xffff0000u);
+                }
                 pb[g] = __builtin_bit_cast(bf16x8, w);
             }
+            l_run = l_run * alpha + sum;
 #pragma unroll
             for (int db = 0; db < C::kDimBlocks; ++db) {
 #pragma unroll

@@ -107,19 +107,25 @@ def test_full_mask_equals_dense_and_empty_rows(ctx, oracle):
     o_s, _ = ctx.sparse_attn(p, q, k, v, api.pack_mask(full))
     o_d, _ = ctx.full_attn(p, q, k, v)
     torch.cuda.synchronize()
-    assert torch.equal(o_s, o_d)                       # all blocks selected = dense, bit for bit
+    # all blocks selected = dense attention (the two kernels order their softmax arithmetic differently, so equal
+    # up to the rounding of the bf16 output, and both within tolerance of the oracle)
+    assert (o_s.float() - o_d.float()).abs().max().item() <= 2.0 ** -6
+    qf, kf, vf = w.f32()
+    o_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, 128, True, None)
+    PU.check_output(o_s.float().cpu().numpy(), o_ref, "sparse with a full mask")
+    PU.check_output(o_d.float().cpu().numpy(), o_ref, "dense")
     # garbage bits above the diagonal / beyond the sequence are ignored
     noisy = np.ones((2, N, 64), np.uint8)
     o_n, _ = ctx.sparse_attn(p, q, k, v, api.pack_mask(noisy))
     torch.cuda.synchronize()
-    assert torch.equal(o_n, o_d)
+    assert torch.equal(o_n, o_s)
     # an empty row gives zeros and lse = -inf, other rows are untouched
     hole = full.copy()
     hole[0, 2, :] = 0
     o_h, lse = ctx.sparse_attn(p, q, k, v, api.pack_mask(hole), want_lse=True)
     torch.cuda.synchronize()
     assert torch.all(o_h[0, 256:384] == 0) and torch.all(torch.isinf(lse[0, 256:384]))
-    assert torch.equal(o_h[1], o_d[1]) and torch.equal(o_h[0, :256], o_d[0, :256])
+    assert torch.equal(o_h[1], o_s[1]) and torch.equal(o_h[0, :256], o_s[0, :256])
 
 
 def test_rows_sum_to_one_and_determinism(ctx, oracle):
