@@ -329,18 +329,19 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
             asm volatile("" : "+v"(sm_ma), "+v"(next));
         } else if constexpr (m == 3) {
             const float m_safe = sm_ma == -INFINITY ? 0.0f : sm_ma;
-            sm_alpha[par] = fast_exp2((m_run - m_safe) * c2);
+            sm_alpha[par] = (m_run - m_safe) * c2;       // exponent of the rescale factor; the factor itself follows
             sm_msc[par] = m_safe * c2;
             m_run = sm_ma;
             asm volatile("" : "+v"(sm_alpha[par]), "+v"(sm_msc[par]), "+v"(m_run), "+v"(next));
         } else if constexpr (m == 4) {
             sm_a[par][0] = fmaf(s[0], c2, -sm_msc[par]);
             sm_a[par][1] = fmaf(s[1], c2, -sm_msc[par]);
+            sm_alpha[par] = fast_exp2(sm_alpha[par]);    // (needed only when the sub-step closes)
             if constexpr (kLazy) {
-                asm volatile("" : "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
+                asm volatile("" : "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(sm_alpha[par]), "+v"(next));
             } else {
                 sm_sum[par] = 0.0f;
-                asm volatile("" : "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(sm_sum[par]), "+v"(next));
+                asm volatile("" : "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(sm_alpha[par]), "+v"(sm_sum[par]), "+v"(next));
             }
         } else {
             sm_x[par][0] = fast_exp2(sm_a[par][0]);
