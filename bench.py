@@ -100,7 +100,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--workload", default="cfg3",
+                    help="cfg1 .. cfg5 (cfg3 is the headline), or rand32k_d64 / rand32k_d128 / rand32k_d256: random "
+                         "GQA 32/8 layer at L = 32K with that head dimension and a fixed 25 %% budget")
     ap.add_argument("--gain", type=float, default=4.0)
     ap.add_argument("--layout", default="htd", choices=["htd", "thd"])
     ap.add_argument("--c-h", type=int, default=0, help="head compression factor (Eq. (2)); 0 = the workload's own (1)")
@@ -119,7 +121,7 @@ def main():
     from paper_2512_14082_amd import api
     from paper_2512_14082_amd import workloads as W
 
-    kw = {} if args.workload in ("cfg4",) else {"gain": args.gain}
+    kw = {} if args.workload == "cfg4" or args.workload.startswith("rand32k") else {"gain": args.gain}
     t0 = time.time()
     w = W.by_name(args.workload, **kw)
     t_gen = time.time() - t0
@@ -131,7 +133,7 @@ def main():
     q, k, v = (api.bits_to_device(x) for x in (w.q, w.k, w.v))
     if args.layout == "thd":
         q, k, v = (x.transpose(0, 1).contiguous() for x in (q, k, v))
-    p = api.Problem(w.cu_seqlens, w.n_heads_q, w.n_heads_kv, w.block_size, w.causal)
+    p = api.Problem(w.cu_seqlens, w.n_heads_q, w.n_heads_kv, w.block_size, w.causal, head_dim=w.head_dim)
     s = api.Select(w.c_q, w.c_k, w.c_h, w.mode, w.param if w.mode == W.TOP_P else 0.9,
                    w.param if w.mode == W.TOP_K else 0.25)
     ws = ctx.alloc_workspace(p, s)
@@ -162,7 +164,10 @@ def main():
 
     # ---- per-kernel timings (HIP events on the launch stream) ------------------------------------
     reps = max(3, args.steps)
-    ms_pool = _time_ms(lambda: (ctx.avgpool_seq(q, s.c_q, lay), ctx.avgpool_seq(k, s.c_k, lay)), reps)
+    if w.head_dim == 128:
+        ms_pool = _time_ms(lambda: (ctx.avgpool_seq(q, s.c_q, lay), ctx.avgpool_seq(k, s.c_k, lay)), reps)
+    else:
+        ms_pool = _time_ms(lambda: (ctx.pool_seq_varlen(p, q, s.c_q, lay), ctx.pool_seq_varlen(p, k, s.c_k, lay)), reps)
     ms_build = _time_ms(lambda: ctx.build_mask(p, s, q, k, lay, workspace=ws, mask=mask), reps)
     ctx.lib.unisparse_build_mask  # scores for the selection-only timing
     _, sc = ctx.build_mask(p, s, q, k, lay, workspace=ws, mask=mask, want_score=True)

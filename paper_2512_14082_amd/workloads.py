@@ -314,7 +314,17 @@ def random_small(H: int = 4, Hkv: int = 2, lengths: Sequence[int] = (256,), S: i
                     gain=0.0, seed=seed)
 
 
+def random_32k(d: int = HEAD_DIM, seed: int = BASE_SEED + 9, **_unused) -> Workload:
+    """GQA 32/8 layer at L = 32K with i.i.d. Gaussian tensors and a fixed 25 % budget: the timing shape for the
+    head dimensions other than 128 (no planted structure; selection at a fixed budget keeps the density known)."""
+    w = random_small(H=32, Hkv=8, lengths=(32768,), S=128, causal=True, mode=TOP_K, param=0.25, seed=seed, d=d)
+    w.name = f"rand32k_gqa32x8_d{d}"
+    return w
+
+
 def by_name(name: str, **kw) -> Workload:
+    if name.startswith("rand32k_d"):
+        return random_32k(d=int(name[len("rand32k_d"):]), **kw)
     table = {
         "cfg1": single_head_planted,
         "cfg2": gqa_planted,
