@@ -144,6 +144,97 @@ def test_score_rows_sum_to_composites_per_block(oracle, cq, ck):
         assert np.all(sc >= 0)
 
 
+def token_window_visibility(L, cq, ck):
+    """Composite-level causal visibility stated on TOKENS, not on composite indices: take the textbook
+    token-level causal matrix (key s may be seen by query t iff s <= t) and call composite key s'
+    visible to composite query t' iff ANY (query token, key token) pair of their two windows is
+    causally allowed.  Windows are the clipped, non-overlapping ones of Eq. (1)."""
+    tok = np.tril(np.ones((L, L), dtype=bool))                 # [query token, key token]
+    Lq, Lk = -(-L // cq), -(-L // ck)
+    vis = np.zeros((Lq, Lk), dtype=bool)
+    for t in range(Lq):
+        for s in range(Lk):
+            vis[t, s] = tok[t * cq:min(L, (t + 1) * cq), s * ck:min(L, (s + 1) * ck)].any()
+    return vis
+
+
+def torch_asymmetric_causal_scores(q, k, S, cq, ck, vis):
+    """Eq. (3)-(4) over a torch softmax of the torch-pooled logits restricted to ``vis``."""
+    L, d = q.shape
+    pool = lambda x, c: torch.nn.functional.avg_pool1d(torch.from_numpy(x).T[None], c, c, ceil_mode=True)[0].T \
+        .to(torch.bfloat16).double()
+    p = pool(q, cq) @ pool(k, ck).T / np.sqrt(d)
+    p = p.masked_fill(~torch.from_numpy(vis), float("-inf"))
+    a = torch.softmax(p, dim=-1).numpy()
+    N = -(-L // S)
+    ref = np.zeros((N, N))
+    for t in range(a.shape[0]):
+        for s in range(a.shape[1]):
+            ref[(t * cq) // S, (s * ck) // S] += a[t, s]          # t' in R_q(i), s' in R_k(j)
+    return np.tril(ref)                                           # block-level cut of Alg. 1 step 4
+
+
+@pytest.mark.parametrize("S", [64, 128])
+@pytest.mark.parametrize("cq,ck", [(32, 2), (16, 4), (4, 16), (2, 32)])
+def test_scores_asymmetric_causal_match_token_window_visibility(oracle, cq, ck, S):
+    """Pins the valid attention range of a composite query when c_q != c_k (Sec. 5 "Fused Kernel
+    Optimization"; the shapes of the ablation "Q-K Compression Ratio Allocation") against a visibility
+    matrix built from explicit token windows.  Two other plausible rules are shown to give different
+    scores on the same input, so the pin is sensitive to the choice."""
+    rng = np.random.default_rng(17 + cq)
+    L, d = 4 * S, 32
+    q = bf16_values(rng, (L, d), 1.3)
+    k = bf16_values(rng, (L, d), 1.3)
+    vis = token_window_visibility(L, cq, ck)
+    ref = torch_asymmetric_causal_scores(q, k, S, cq, ck, vis)
+    got = oracle.block_scores(q[None], k[None], [0, L], S, cq, ck, True)[0]
+    np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-13)
+    # alternative rules, again on token windows: (a) the key window must start no later than the FIRST
+    # token of the query window; (b) the key window must END no later than the query window's last token
+    tok = np.tril(np.ones((L, L), dtype=bool))
+    Lq, Lk = L // cq, L // ck
+    vis_a = np.array([[tok[t * cq, s * ck] for s in range(Lk)] for t in range(Lq)])
+    vis_b = np.array([[tok[(t + 1) * cq - 1, (s + 1) * ck - 1] for s in range(Lk)] for t in range(Lq)])
+    vis_b[:, 0] |= ~vis_b.any(axis=1)                             # keep rule (b) free of empty rows
+    # with nested windows (a) can differ only when the query window is the longer one, (b) only when the
+    # key window is: each is the plausible mistake for one half of the table's shapes
+    other = vis_a if cq > ck else vis_b
+    assert (other != vis).any()
+    alt = torch_asymmetric_causal_scores(q, k, S, cq, ck, other)
+    assert np.abs(alt - got).max() > 1e-3
+
+
+def test_scores_asymmetric_causal_ragged_length(oracle):
+    """Same pin with a length that neither S nor the compression factors divide."""
+    rng = np.random.default_rng(18)
+    L, d, S = 203, 32, 64
+    q = bf16_values(rng, (L, d), 1.3)
+    k = bf16_values(rng, (L, d), 1.3)
+    for cq, ck in [(4, 16), (16, 4)]:
+        ref = torch_asymmetric_causal_scores(q, k, S, cq, ck, token_window_visibility(L, cq, ck))
+        got = oracle.block_scores(q[None], k[None], [0, L], S, cq, ck, True)[0]
+        np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-13)
+
+
+def test_scores_asymmetric_causal_constant_input_hand_worked(oracle):
+    """Constant Q = K: every visible composite key of a row gets the same weight, so the scores are
+    counts worked out by hand from the token windows (L = 16, S = 8, two blocks).
+
+    c_q = 4, c_k = 2: query windows end at tokens 3, 7, 11, 15; key windows start at 0, 2, ..., 14.
+      visible keys per composite query: 2, 4, 6, 8.  Block 1 holds queries 2 and 3, block 0 keys 0..3:
+      Score(1,0) = 4/6 + 4/8 = 7/6,  Score(1,1) = 2/6 + 4/8 = 5/6,  Score(0,0) = 2/2 + 4/4 = 2.
+    c_q = 2, c_k = 4: query windows end at 1, 3, 5, ..., 15; key windows start at 0, 4, 8, 12.
+      visible keys per composite query: 1, 1, 2, 2, 3, 3, 4, 4.  Block 1 holds queries 4..7, block 0 keys 0, 1:
+      Score(1,0) = 2/3 + 2/3 + 2/4 + 2/4 = 7/3,  Score(1,1) = 1/3 + 1/3 + 2/4 + 2/4 = 5/3,  Score(0,0) = 4.
+    ("starts no later than the first query token" would give 4/5 + 4/7 in the first case; "ends no later than
+    the last query token" would leave composite query 0 of the second case without any key.)"""
+    x = np.full((1, 16, 8), 0.5, np.float32)
+    sc = oracle.block_scores(x, x, [0, 16], 8, 4, 2, True)[0]
+    np.testing.assert_allclose(sc, [[2.0, 0.0], [7.0 / 6.0, 5.0 / 6.0]], rtol=1e-12)
+    sc = oracle.block_scores(x, x, [0, 16], 8, 2, 4, True)[0]
+    np.testing.assert_allclose(sc, [[4.0, 0.0], [7.0 / 3.0, 5.0 / 3.0]], rtol=1e-12)
+
+
 def test_scores_constant_input_closed_form(oracle):
     L, d, S, c = 256, 16, 32, 4
     x = np.full((1, L, d), 0.5, np.float32)
