@@ -107,6 +107,8 @@ def main():
     ap.add_argument("--layout", default="htd", choices=["htd", "thd"])
     ap.add_argument("--c-h", type=int, default=0, help="head compression factor (Eq. (2)); 0 = the workload's own (1)")
     ap.add_argument("--c", type=int, default=0, help="sequence compression factor c_q = c_k; 0 = the workload's own (8)")
+    ap.add_argument("--param", type=float, default=0.0,
+                    help="selection threshold P (Top-P workloads) or kept fraction f (budget workloads); 0 = the workload's own")
     ap.add_argument("--dense-reps", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--profile-copy-mb", type=int, default=0,
@@ -129,6 +131,8 @@ def main():
         w.c_h = args.c_h
     if args.c > 0:
         w.c_q = w.c_k = args.c
+    if args.param > 0:
+        w.param = args.param
     ctx = api.Context(0)
     q, k, v = (api.bits_to_device(x) for x in (w.q, w.k, w.v))
     if args.layout == "thd":
@@ -169,7 +173,7 @@ def main():
     else:
         ms_pool = _time_ms(lambda: (ctx.pool_seq_varlen(p, q, s.c_q, lay), ctx.pool_seq_varlen(p, k, s.c_k, lay)), reps)
     ms_build = _time_ms(lambda: ctx.build_mask(p, s, q, k, lay, workspace=ws, mask=mask), reps)
-    ctx.lib.unisparse_build_mask  # scores for the selection-only timing
+    # scores for the selection-only timing
     _, sc = ctx.build_mask(p, s, q, k, lay, workspace=ws, mask=mask, want_score=True)
     ms_select = _time_ms(lambda: ctx.select_blocks(p, s, sc, mask=mask), reps)
     ms_sparse = _time_ms(lambda: ctx.sparse_attn(p, q, k, v, mask, lay, out=o), reps)

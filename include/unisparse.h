@@ -33,9 +33,11 @@
  *   are ignored (treated as 0) by sparse_attn.
  * - Errors: every call validates its arguments on the host before launching anything and
  *   returns a status; on error no kernel is launched and no output is touched.  Launch
- *   failures reported by HIP map to UNISPARSE_ERR_HIP.
+ *   failures reported by HIP map to UNISPARSE_ERR_HIP; an error that earlier work of the caller left pending in
+ *   the runtime (hipGetLastError) is cleared on entry and not reported.
  * - stream arguments are hipStream_t values passed as void* (NULL = the null stream).  Work goes to the device
- *   that is current in the calling thread, which must be the stream's device.
+ *   the context was created for; it must be the device current in the calling thread and the stream's device
+ *   (UNISPARSE_ERR_PARAM if another device is current).
  * - The first launch of a kernel on a device raises that kernel's dynamic-LDS limit (a host-side HIP call), so a
  *   stream capture should follow one ordinary call of the same entry point with the same configuration; after
  *   that the calls are launches only - no allocation, no memset, no synchronisation.
@@ -55,7 +57,7 @@ extern "C" {
 #define UNISPARSE_HEAD_DIM 128       /* the default head dimension (and that of unisparse_avgpool_seq) */
 #define UNISPARSE_MAX_BLOCKS_PER_SEQ 4096   /* NK limit (selection keeps one row in a wavefront's registers) */
 
-typedef struct unisparse_ctx unisparse_ctx;   /* opaque; caches device properties only */
+typedef struct unisparse_ctx unisparse_ctx;   /* opaque; the device it was created for and its compute-unit count */
 
 typedef enum {
     UNISPARSE_OK = 0,

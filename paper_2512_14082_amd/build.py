@@ -43,21 +43,7 @@ def build_library(extra_flags=(), verbose: bool = True) -> str:
         raise RuntimeError("link failed:\n" + r.stderr)
     if verbose:
         print(f"built {LIB}")
-    build_probe(verbose)
     return LIB
-
-
-def build_probe(verbose: bool = True) -> str:
-    """Compile the stand-alone MFMA rate probe (csrc/probe_mfma.hip) next to the library."""
-    exe = os.path.join(HERE, "probe_mfma")
-    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           os.path.join(CSRC, "probe_mfma.hip"), "-o", exe]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("probe_mfma build failed:\n" + r.stderr)
-    if verbose:
-        print(f"built {exe}")
-    return exe
 
 
 if __name__ == "__main__":

@@ -8,8 +8,7 @@
 
 struct unisparse_ctx {
     int device;
-    int n_cu;
-    size_t lds_per_block;
+    int n_cu;        // compute units: sizes the score kernel's grid rule
 };
 
 namespace {
@@ -23,6 +22,19 @@ struct Geom {
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Common preamble of every launching entry point: the context's device must be the one current in the calling
+// thread (kernels go to the current device), and an error that earlier, unrelated work left behind in the runtime is
+// cleared so that the launch checks below report this library's launches only.
+unisparse_status enter(const unisparse_ctx *ctx)
+{
+    if (ctx == nullptr) return UNISPARSE_ERR_NULL;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return UNISPARSE_ERR_HIP;
+    if (dev != ctx->device) return UNISPARSE_ERR_PARAM;
+    (void)hipGetLastError();
+    return UNISPARSE_OK;
+}
 
 unisparse_status check_problem(const unisparse_problem *p, Geom *g)
 {
@@ -168,7 +180,7 @@ unisparse_status select_impl(const unisparse_problem *p, const unisparse_select 
     return launch_select(sa, stream) == hipSuccess ? UNISPARSE_OK : UNISPARSE_ERR_HIP;
 }
 
-unisparse_status attn_impl(const unisparse_problem *p, const Geom &g, unisparse_tensor Q, unisparse_tensor K,
+unisparse_status attn_impl(const unisparse_ctx *ctx, const unisparse_problem *p, const Geom &g, unisparse_tensor Q, unisparse_tensor K,
                            unisparse_tensor V, const uint64_t *M, unisparse_tensor O, float *lse,
                            hipStream_t stream)
 {
@@ -177,6 +189,7 @@ unisparse_status attn_impl(const unisparse_problem *p, const Geom &g, unisparse_
     if ((st = check_tensor(K, p->head_dim)) != UNISPARSE_OK) return st;
     if ((st = check_tensor(V, p->head_dim)) != UNISPARSE_OK) return st;
     if ((st = check_tensor(O, p->head_dim)) != UNISPARSE_OK) return st;
+    if ((st = enter(ctx)) != UNISPARSE_OK) return st;
     AttnArgs a;
     a.q = view(Q);
     a.k = view(K);
@@ -210,11 +223,16 @@ unisparse_status unisparse_create(unisparse_ctx **ctx, int device)
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) return UNISPARSE_ERR_HIP;
     if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return UNISPARSE_ERR_UNSUPPORTED;
+    // the work orders of the kernels deal workgroups to kNumXcd dies with a private L2 each
+    int n_xcd = 0;
+    if (hipDeviceGetAttribute(&n_xcd, hipDeviceAttributeNumberOfXccs, device) == hipSuccess && n_xcd > 0 &&
+        n_xcd != kNumXcd)
+        return UNISPARSE_ERR_UNSUPPORTED;
+    (void)hipGetLastError();
     unisparse_ctx *c = new (std::nothrow) unisparse_ctx;
     if (c == nullptr) return UNISPARSE_ERR_HIP;
     c->device = device;
     c->n_cu = prop.multiProcessorCount;
-    c->lds_per_block = prop.sharedMemPerBlock;
     *ctx = c;
     return UNISPARSE_OK;
 }
@@ -271,6 +289,7 @@ unisparse_status unisparse_avgpool_seq(unisparse_ctx *ctx, unisparse_tensor x, i
     if (st != UNISPARSE_OK) return st;
     if (n_heads < 1 || total_tokens < 0 || c < 1 || total_tokens % c != 0) return UNISPARSE_ERR_SHAPE;
     if (((uintptr_t)out & 15) != 0) return UNISPARSE_ERR_SHAPE;
+    if ((st = enter(ctx)) != UNISPARSE_OK) return st;
     hipError_t e = launch_avgpool_seq(view(x), n_heads, total_tokens, c, UNISPARSE_POOL_AVG, UNISPARSE_HEAD_DIM,
                                       reinterpret_cast<bf16_t *>(out),
                                       (hipStream_t)stream);
@@ -291,6 +310,7 @@ unisparse_status unisparse_pool_seq_varlen(unisparse_ctx *ctx, const unisparse_p
     if (((uintptr_t)out & 15) != 0) return UNISPARSE_ERR_SHAPE;
     if (pool == UNISPARSE_POOL_STOCHASTIC && rand == nullptr) return UNISPARSE_ERR_NULL;
     if (pool == UNISPARSE_POOL_STOCHASTIC && c > 32) return UNISPARSE_ERR_UNSUPPORTED;
+    if ((st = enter(ctx)) != UNISPARSE_OK) return st;
     hipError_t e = pool == UNISPARSE_POOL_STOCHASTIC
                        ? launch_stochpool_seq_varlen(view(x), n_heads, g.st, c, p->head_dim, rand, reinterpret_cast<bf16_t *>(out),
                                                      (hipStream_t)stream)
@@ -316,6 +336,7 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     unsigned char *base = reinterpret_cast<unsigned char *>(align256((size_t)(uintptr_t)workspace));
     const size_t lead = (size_t)(base - reinterpret_cast<unsigned char *>(workspace));
     if (workspace_bytes < w.total + lead) return UNISPARSE_ERR_WORKSPACE;
+    if ((st = enter(ctx)) != UNISPARSE_OK) return st;
     if (g.T == 0) return UNISPARSE_OK;
     hipStream_t stream = (hipStream_t)stream_;
 
@@ -364,6 +385,7 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     pa.NQ = g.NQ;
     pa.NK = g.NK;
     pa.scale_log2 = scale_log2(p);
+    pa.n_cu = ctx->n_cu;
     if (launch_proxy_scores(pa, stream) != hipSuccess) return UNISPARSE_ERR_HIP;
     return select_impl(p, s, g, hg, sc, M, stream);
 }
@@ -378,6 +400,7 @@ unisparse_status unisparse_select_blocks(unisparse_ctx *ctx, const unisparse_pro
     unisparse_status st;
     if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
     if ((st = check_select(p, s, &hg)) != UNISPARSE_OK) return st;
+    if ((st = enter(ctx)) != UNISPARSE_OK) return st;
     if (g.T == 0) return UNISPARSE_OK;
     return select_impl(p, s, g, hg, score, M, (hipStream_t)stream);
 }
@@ -392,7 +415,7 @@ unisparse_status unisparse_sparse_attn(unisparse_ctx *ctx, const unisparse_probl
     unisparse_status st;
     if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
     if (g.T == 0) return check_tensor(Q, p->head_dim);
-    return attn_impl(p, g, Q, K, V, M, O, lse, (hipStream_t)stream);
+    return attn_impl(ctx, p, g, Q, K, V, M, O, lse, (hipStream_t)stream);
 }
 
 unisparse_status unisparse_full_attn(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor Q,
@@ -404,7 +427,7 @@ unisparse_status unisparse_full_attn(unisparse_ctx *ctx, const unisparse_problem
     unisparse_status st;
     if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
     if (g.T == 0) return check_tensor(Q, p->head_dim);
-    return attn_impl(p, g, Q, K, V, nullptr, O, lse, (hipStream_t)stream);
+    return attn_impl(ctx, p, g, Q, K, V, nullptr, O, lse, (hipStream_t)stream);
 }
 
 unisparse_status unisparse_attn(unisparse_ctx *ctx, const unisparse_problem *p, const unisparse_select *s,

@@ -133,6 +133,7 @@ struct ProxyArgs {
     int32_t NQ, NK;
     int32_t head_dim;        // d
     int32_t tiles;           // 32-row tiles per wavefront: 0 = automatic, 1 or 2 forced
+    int32_t n_cu;            // compute units of the device (for the automatic choice)
     float scale_log2;        // softmax scale * log2(e)
 };
 hipError_t launch_proxy_scores(const ProxyArgs &a, hipStream_t stream);

@@ -34,7 +34,7 @@ hipError_t launch_proxy_scores(const ProxyArgs &a, hipStream_t stream)
             g.n_tiles += (lq + rows_per_tile - 1) / rows_per_tile;
         }
         nblk = (int64_t)a.n_heads_kv * g.GS * g.n_tiles;
-        const bool want_one = a.tiles == 1 || (a.tiles == 0 && nblk < 4 * 256);
+        const bool want_one = a.tiles == 1 || (a.tiles == 0 && nblk < 4 * (int64_t)a.n_cu);
         if (!(want_one && g.QT == 2 && proxy_has_single_tile(a.head_dim, a.S / a.c_q))) break;
     }
     if (nblk == 0) return hipSuccess;

@@ -45,9 +45,11 @@ def row_geometry(cu, S):
     return np.array(loc), np.array(nb)
 
 
-def check_mask_against_oracle(m_gpu, m_ref, score_ref, cu, S, causal, mode, param, rows=None):
+def check_mask_against_oracle(m_gpu, m_ref, score_ref, cu, S, causal, mode, param, rows=None, counts=None):
     """>= 99.9 % of valid decisions equal; every mismatch admissible: the oracle's normalised score of the
-    block lies within 1e-3 of the row's cut, or (Top-P) the cumulative share next to it lies within 1e-3 of P."""
+    block lies within 1e-3 of the row's cut, or (Top-P) the cumulative share next to it lies within 1e-3 of P.
+    ``counts`` (a two-element list) accumulates [mismatches, valid decisions] over several calls; the agreement
+    bound is then the caller's to assert on the total."""
     loc, nb = row_geometry(cu, S)
     H, NQ, NK = m_ref.shape
     c_h = H // score_ref.shape[0]
@@ -78,6 +80,10 @@ def check_mask_against_oracle(m_gpu, m_ref, score_ref, cu, S, causal, mode, para
                     ok = ok or abs(before - param) <= CUT_TOL or abs(cum[pos[j]] - param) <= CUT_TOL
                 assert ok, f"inadmissible mask mismatch h={h} row={r} j={j} p={p[j]:.3e} tau={tau:.3e}"
     agree = 1.0 - n_bad / max(1, n_valid)
+    if counts is not None:
+        counts[0] += n_bad
+        counts[1] += n_valid
+        return agree
     assert agree >= MASK_AGREE_MIN, f"mask agreement {agree:.5f}"
     return agree
 
@@ -148,3 +154,111 @@ def full_pipeline_check(ctx, oracle, w: W.Workload, layout="htd", check_dense=Tr
         od_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, w.block_size, w.causal, None, rows=rows)
         check_output(to_htd(od_dev, layout).float().cpu().numpy(), od_ref, "dense")
     return agree
+
+
+def say(msg):
+    """Progress line of a long test (visible with -s; flushed so that a run that dies still names its step)."""
+    print(msg, flush=True)
+
+
+def sampled_rows(w: W.Workload, pop_h, rng, n_random):
+    """Query-block rows one head is checked on at full size: the first and last row of every sequence, the rows
+    with the fewest and the most selected blocks, and ``n_random`` seeded rows."""
+    rows, base = set(), 0
+    for n in w.n_blocks():
+        if n > 0:
+            rows.update((base, base + n - 1))
+        base += n
+    rows.update((int(np.argmin(pop_h)), int(np.argmax(pop_h))))
+    rows.update(int(x) for x in rng.integers(0, len(pop_h), n_random))
+    return sorted(rows)
+
+
+def sampled_config_check(ctx, oracle, w: W.Workload, seed, n_random=16, attn_heads=(0,), attn_random=1,
+                         dense_heads=(0,), extra_thresholds=()):
+    """A benchmark configuration at its own shape: the whole GPU path exactly as bench.py launches it (mask with
+    workspace, block-sparse attention, dense attention), the oracle on sampled outputs.
+
+    Mask and scores: per query head, the rows of ``sampled_rows``.  Selection: bit-exact against the oracle's
+    selection applied to the GPU's own scores on EVERY row.  Attention: for the heads of ``attn_heads`` the first
+    and last row of every sequence, the head's rows of least and most selected blocks and ``attn_random`` seeded rows;
+    dense attention on the last row and one seeded row of ``dense_heads``.  ``extra_thresholds``: further Top-P
+    thresholds run through unisparse_select_blocks on the same score buffer, checked the same way.
+    Returns {"agreement", "density", "densities": {P: density}}."""
+    rng = np.random.default_rng(seed)
+    S, H, G = w.block_size, w.n_heads_q, w.n_heads_q // w.n_heads_kv
+    q, k, v = device_tensors(w)
+    qf, kf, vf = w.f32()
+    p, s = problem_of(w), select_of(w)
+    ws, m_dev = ctx.alloc_workspace(p, s), ctx.alloc_mask(p)
+    ctx.build_mask(p, s, q, k, workspace=ws, mask=m_dev)                  # as the benchmark calls it
+    _, sc_dev = ctx.build_mask(p, s, q, k, workspace=ws, mask=ctx.alloc_mask(p), want_score=True)
+    o_dev, lse_dev = ctx.sparse_attn(p, q, k, v, m_dev, want_lse=True)
+    od_dev, _ = ctx.full_attn(p, q, k, v)
+    torch.cuda.synchronize()
+    m_gpu = api.unpack_mask(m_dev, p.n_cols)
+    sc_gpu = sc_dev.cpu().numpy()
+    loc, nb = row_geometry(w.cu_seqlens, S)
+    NQ, NK = m_gpu.shape[1], m_gpu.shape[2]
+    valid = (np.arange(NK)[None, :] <= loc[:, None]) if w.causal else (np.arange(NK)[None, :] < nb[:, None])
+    n_valid_head = int(valid.sum())
+    # -- structure that holds on every row
+    assert not (m_gpu & ~valid[None]).any(), "bit outside the valid set"
+    assert m_gpu.any(-1).all(), "empty mask row"
+    assert not (sc_gpu * ~valid[None]).any(), "score outside the valid set"
+    whole = np.array([all((w.cu_seqlens[b + 1] - w.cu_seqlens[b]) % S == 0 for b in range(len(w.cu_seqlens) - 1))])
+    if whole.all():
+        np.testing.assert_allclose(sc_gpu.sum(-1), S / w.c_q, rtol=1e-3)       # every composite row of A~ sums to 1
+    density = float(m_gpu.sum()) / (H * n_valid_head)
+    say(f"{w.name}: GPU path done, density {density:.4f}")
+    # -- selection is index work: on the GPU's own scores it must equal the oracle's on every row
+    m_sel = oracle.select_mask(sc_gpu, w.cu_seqlens, S, w.causal, w.mode, w.param)
+    assert np.array_equal(m_gpu, m_sel), "selection differs from the oracle on identical scores"
+    # -- scores and mask against the oracle's own scores, sampled rows per head
+    pop = m_gpu.sum(-1)
+    counts = [0, 0]
+    ref = {}
+    for h in range(H):
+        rows = sampled_rows(w, pop[h], rng, n_random)
+        m_ref, sc_ref = oracle.build_mask(qf[h:h + 1], kf[h // G:h // G + 1], w.cu_seqlens, S, w.c_q, w.c_k, w.causal,
+                                          w.mode, w.param, rows=rows)
+        np.testing.assert_allclose(sc_gpu[h, rows], sc_ref[0, rows], rtol=2e-3, atol=1e-6)
+        check_mask_against_oracle(m_gpu[h:h + 1], m_ref, sc_ref, w.cu_seqlens, S, w.causal, w.mode, w.param, rows, counts)
+        ref[h] = (rows, sc_ref)
+    agree = 1.0 - counts[0] / counts[1]
+    say(f"{w.name}: mask agreement {agree:.6f} over {counts[1]} sampled decisions ({counts[0]} admissible mismatches)")
+    assert agree >= MASK_AGREE_MIN, f"mask agreement {agree:.5f}"
+    result = {"agreement": agree, "density": density, "densities": {w.param: density}}
+    # -- further thresholds on the same score buffer (selection only)
+    for P in extra_thresholds:
+        s_p = select_of(w)
+        s_p.threshold = P
+        m_p = api.unpack_mask(ctx.select_blocks(p, s_p, sc_dev.clone()), p.n_cols)
+        torch.cuda.synchronize()
+        assert np.array_equal(m_p, oracle.select_mask(sc_gpu, w.cu_seqlens, S, w.causal, w.mode, P)), f"P={P}"
+        cnt = [0, 0]
+        for h in range(H):
+            rows, sc_ref = ref[h]
+            m_ref = oracle.select_mask(sc_ref, w.cu_seqlens, S, w.causal, w.mode, P, rows)
+            check_mask_against_oracle(m_p[h:h + 1], m_ref, sc_ref, w.cu_seqlens, S, w.causal, w.mode, P, rows, cnt)
+        a_p = 1.0 - cnt[0] / cnt[1]
+        result["densities"][P] = float(m_p.sum()) / (H * n_valid_head)
+        say(f"{w.name}: P = {P}: density {result['densities'][P]:.4f}, mask agreement {a_p:.6f}")
+        assert a_p >= MASK_AGREE_MIN, f"P={P}: mask agreement {a_p:.5f}"
+    # -- attention on the GPU's own mask, sampled (head, row) outputs
+    o_gpu = o_dev.float().cpu().numpy()
+    lse_gpu = lse_dev.cpu().numpy()
+    for h in attn_heads:
+        rows = sampled_rows(w, pop[h], rng, attn_random)
+        o_ref, lse_ref = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, S, w.causal, m_gpu, rows=rows, heads=[h])
+        mx, mean = check_output(o_gpu[h:h + 1], o_ref[h:h + 1], f"{w.name} sparse head {h}")
+        ls = ~np.isnan(lse_ref[h])
+        np.testing.assert_allclose(lse_gpu[h][ls], lse_ref[h][ls], rtol=1e-3, atol=2e-3)
+        say(f"{w.name}: sparse attention head {h} rows {rows}: max-abs {mx:.4f} mean-abs {mean:.5f}")
+    od_gpu = od_dev.float().cpu().numpy()
+    for h in dense_heads:
+        rows = sorted({NQ - 1, int(rng.integers(0, NQ))})
+        od_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, S, w.causal, None, rows=rows, heads=[h])
+        mx, mean = check_output(od_gpu[h:h + 1], od_ref[h:h + 1], f"{w.name} dense head {h}")
+        say(f"{w.name}: dense attention head {h} rows {rows}: max-abs {mx:.4f} mean-abs {mean:.5f}")
+    return result

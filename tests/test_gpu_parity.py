@@ -191,56 +191,36 @@ def test_error_paths(ctx):
 
 
 def test_config2_shape_sampled_rows(ctx, oracle):
-    """Llama-3-8B-shaped layer at L = 32K: full GPU run, oracle on sampled query-block rows."""
-    w = W.gqa_planted()
-    rng = np.random.default_rng(1)
-    rows = sorted({0, 1, 255, *[int(x) for x in rng.integers(2, 255, 5)]})
-    q, k, v = PU.device_tensors(w)
-    qf, kf, vf = w.f32()
-    p, s = PU.problem_of(w), PU.select_of(w)
-    m_dev, sc_dev = ctx.build_mask(p, s, q, k, want_score=True)
-    torch.cuda.synchronize()
-    m_gpu = api.unpack_mask(m_dev, p.n_cols)
-    m_ref, sc_ref = oracle.build_mask(qf, kf, w.cu_seqlens, 128, 8, 8, True, w.mode, w.param, rows=rows)
-    np.testing.assert_allclose(sc_dev.cpu().numpy()[:, rows], sc_ref[:, rows], rtol=2e-3, atol=1e-6)
-    PU.check_mask_against_oracle(m_gpu, m_ref, sc_ref, w.cu_seqlens, 128, True, w.mode, w.param, rows)
-    density = m_gpu.sum() / (32 * 256 * 257 / 2)
-    print("cfg2 density", density)
-    o_dev, _ = ctx.sparse_attn(p, q, k, v, m_dev)
-    torch.cuda.synchronize()
-    heads = [0, 13, 31]
-    o_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, 128, True, m_gpu, rows=rows[:4], heads=heads)
-    PU.check_output(o_dev.float().cpu().numpy()[heads], o_ref[heads], "cfg2 sparse")
+    """Llama-3-8B-shaped layer at L = 32K (GQA 32/8, Top-P 0.95): full GPU run, oracle on sampled outputs."""
+    r = PU.sampled_config_check(ctx, oracle, W.gqa_planted(), seed=1, attn_heads=(0, 13, 31), dense_heads=(5,))
+    assert 0.2 < r["density"] < 0.8
 
 
 def test_config3_headline_shape_sampled_rows(ctx, oracle):
-    """The benchmarked configuration itself (GQA 32/8, L = 128K, S = 128, Top-P 0.9): full GPU run of the mask,
-    the block-sparse and the dense kernel as bench.py launches them, oracle on sampled query-block rows."""
-    w = W.gqa_zipf()
-    N = w.n_blocks()[0]
-    rng = np.random.default_rng(3)
-    rows = sorted({0, 1, N - 1, *[int(x) for x in rng.integers(2, N - 1, 5)]})
-    q, k, v = PU.device_tensors(w)
-    qf, kf, vf = w.f32()
-    p, s = PU.problem_of(w), PU.select_of(w)
-    m_dev, sc_dev = ctx.build_mask(p, s, q, k, want_score=True)
-    torch.cuda.synchronize()
-    m_gpu = api.unpack_mask(m_dev, p.n_cols)
-    m_ref, sc_ref = oracle.build_mask(qf, kf, w.cu_seqlens, w.block_size, w.c_q, w.c_k, True, w.mode, w.param, rows=rows)
-    np.testing.assert_allclose(sc_dev.cpu().numpy()[:, rows], sc_ref[:, rows], rtol=2e-3, atol=1e-6)
-    PU.check_mask_against_oracle(m_gpu, m_ref, sc_ref, w.cu_seqlens, w.block_size, True, w.mode, w.param, rows)
-    # structure that holds at any size: nothing above the diagonal, no empty row, score rows sum to S / c_q
-    assert not np.triu(m_gpu, 1).any() and m_gpu.any(-1).all()
-    np.testing.assert_allclose(np.tril(sc_dev.cpu().numpy()).sum(-1), w.block_size / w.c_q, rtol=1e-3)
-    o_dev, _ = ctx.sparse_attn(p, q, k, v, m_dev)
-    od_dev, _ = ctx.full_attn(p, q, k, v)
-    torch.cuda.synchronize()
-    heads = [0, 13, 31]
-    att_rows = [rows[0], rows[3], rows[-1]]
-    o_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, w.block_size, True, m_gpu, rows=att_rows, heads=heads)
-    PU.check_output(o_dev.float().cpu().numpy()[heads], o_ref[heads], "cfg3 sparse")
-    od_ref, _ = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, w.block_size, True, None, rows=att_rows[1:], heads=heads[:2])
-    PU.check_output(od_dev.float().cpu().numpy()[heads[:2]], od_ref[heads[:2]], "cfg3 dense")
+    """The benchmarked configuration itself (GQA 32/8, L = 128K, S = 128, Top-P 0.9): the mask, the block-sparse and
+    the dense kernel as bench.py launches them; selection bit-exact on all 32768 rows, scores / mask on ~20 rows of
+    every head, attention on 5-6 rows of three heads (sparse) and two rows of two heads (dense)."""
+    r = PU.sampled_config_check(ctx, oracle, W.gqa_zipf(), seed=3, attn_heads=(0, 13, 31), dense_heads=(2, 29))
+    assert 0.2 < r["density"] < 0.5
+
+
+def test_config4_video_shape_sampled_rows(ctx, oracle):
+    """Configuration 4 at its own shape: 40 heads without grouping, 64K tokens of a 16 x 64 x 64 grid, non-causal,
+    fixed 20 % budget (512 key blocks per row: eight mask words, every key block valid on every row)."""
+    w = W.video_field()
+    r = PU.sampled_config_check(ctx, oracle, w, seed=4, attn_heads=(0, 17, 39), dense_heads=(21,))
+    assert abs(r["density"] - np.ceil(0.2 * 512) / 512) < 1e-9            # the budget is met exactly on every row
+
+
+def test_config5_packed_shape_threshold_sweep(ctx, oracle):
+    """Configuration 5 at its own shape: four packed causal sequences of 8K, 16K, 32K and 64K tokens (GQA 32/8) in one
+    launch, and the threshold sweep P in {0.8, 0.9, 0.95, 0.99} through unisparse_select_blocks on one score buffer:
+    density must grow with P."""
+    w = W.gqa_varlen()
+    r = PU.sampled_config_check(ctx, oracle, w, seed=5, attn_heads=(0, 14, 31), attn_random=3, dense_heads=(9,),
+                                extra_thresholds=(0.8, 0.95, 0.99))
+    d = r["densities"]
+    assert d[0.8] < d[0.9] < d[0.95] < d[0.99] <= 1.0
 
 
 def test_empty_sequences_in_the_batch(ctx, oracle):
