@@ -179,6 +179,23 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
                                       void *stream);
 
 /*
+ * unisparse_build_mask for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same kernels, with the composite tokens and the block
+ * scores in a workspace that is part of the library's device image instead of a caller's buffer.  The call
+ * allocates nothing and frees nothing.
+ *   limit : unisparse_workspace_bytes(p, s) <= UNISPARSE_STATIC_WORKSPACE_BYTES (64 MiB; e.g. GQA 32/8 at
+ *           32K tokens with c = 8 needs 48 MiB), else UNISPARSE_ERR_WORKSPACE and nothing is launched
+ *   M     : out, uint64 [H][NQ][W] as for unisparse_build_mask; the scores are not returned
+ * Every device keeps one copy of that workspace for the life of the process, shared by all contexts and all
+ * calls on the device: it holds the previous call's contents (nothing in it needs clearing - every value read is
+ * written earlier in the same call), and calls that overlap in time on one device race on it.
+ */
+#define UNISPARSE_STATIC_WORKSPACE_BYTES (64u << 20)
+unisparse_status unisparse_build_mask_static(unisparse_ctx *ctx, const unisparse_problem *p,
+                                             const unisparse_select *s, unisparse_tensor Q, unisparse_tensor K,
+                                             uint64_t *M, void *stream);
+
+/*
  * Selection only (Alg. 1 step 4) on caller-provided scores, e.g. to re-select with another threshold.
  *   score : float [H / c_h][NQ][NK] (read; entries outside a row's valid set are overwritten with 0)
  */

@@ -25,7 +25,7 @@ EXPORTS = [
     "unisparse_create", "unisparse_destroy", "unisparse_status_string", "unisparse_mask_row_words",
     "unisparse_mask_words", "unisparse_score_elems", "unisparse_workspace_bytes", "unisparse_avgpool_seq",
     "unisparse_pool_seq_varlen",
-    "unisparse_build_mask", "unisparse_select_blocks", "unisparse_sparse_attn", "unisparse_full_attn",
+    "unisparse_build_mask", "unisparse_build_mask_static", "unisparse_select_blocks", "unisparse_sparse_attn", "unisparse_full_attn",
     "unisparse_attn",
 ]
 
@@ -83,6 +83,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.unisparse_pool_seq_varlen.restype = ctypes.c_int
     lib.unisparse_build_mask.argtypes = [vp, PP, SP, _Tensor, _Tensor, vp, sz, vp, vp, vp]
     lib.unisparse_build_mask.restype = ctypes.c_int
+    lib.unisparse_build_mask_static.argtypes = [vp, PP, SP, _Tensor, _Tensor, vp, vp]
+    lib.unisparse_build_mask_static.restype = ctypes.c_int
     lib.unisparse_select_blocks.argtypes = [vp, PP, SP, vp, vp, vp]
     lib.unisparse_select_blocks.restype = ctypes.c_int
     lib.unisparse_sparse_attn.argtypes = [vp, PP, _Tensor, _Tensor, _Tensor, vp, _Tensor, vp, vp]
@@ -253,6 +255,13 @@ class Context:
         _check(self.lib.unisparse_build_mask(self.handle, p.c, s.c, _view(q, layout), _view(k, layout),
                                              ws.data_ptr(), ws.numel(), m.data_ptr(), sp, _stream()))
         return m, score
+
+    def build_mask_static(self, p: Problem, s: Select, q: torch.Tensor, k: torch.Tensor, mask: torch.Tensor,
+                          layout: str = "htd") -> torch.Tensor:
+        """``unisparse_build_mask_static``: the mask into the caller's ``mask``; nothing is allocated."""
+        _check(self.lib.unisparse_build_mask_static(self.handle, p.c, s.c, _view(q, layout), _view(k, layout),
+                                                    mask.data_ptr(), _stream()))
+        return mask
 
     def tune(self, p: Problem, s: Select, q: torch.Tensor, k: torch.Tensor, layout: str = "htd", reps: int = 3) -> Select:
         """Time ``build_mask`` with each tiling of the score kernel this problem admits (``proxy_tiles`` 1 and 2) and

@@ -9,7 +9,13 @@
 struct unisparse_ctx {
     int device;
     int n_cu;        // compute units: sizes the score kernel's grid rule
+    void *scratch;   // this device's copy of the static workspace below (its device address)
 };
+
+// Workspace of unisparse_build_mask_static: composite tokens and block scores of one call.  Every device the
+// library is loaded on holds a copy until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels are given the address that call returns for the context's device.
+static __device__ __align__(256) unsigned char scratch[UNISPARSE_STATIC_WORKSPACE_BYTES];
 
 namespace {
 
@@ -229,8 +235,17 @@ unisparse_status unisparse_create(unisparse_ctx **ctx, int device)
         n_xcd != kNumXcd)
         return UNISPARSE_ERR_UNSUPPORTED;
     (void)hipGetLastError();
+    // device address of this device's copy of the static workspace (looked up with that device current)
+    int prev = -1;
+    if (hipGetDevice(&prev) != hipSuccess) return UNISPARSE_ERR_HIP;
+    if (prev != device && hipSetDevice(device) != hipSuccess) return UNISPARSE_ERR_HIP;
+    void *scratch_ptr = nullptr;
+    const hipError_t se = hipGetSymbolAddress(&scratch_ptr, HIP_SYMBOL(scratch));
+    if (prev != device && hipSetDevice(prev) != hipSuccess) return UNISPARSE_ERR_HIP;
+    if (se != hipSuccess || scratch_ptr == nullptr) return UNISPARSE_ERR_HIP;
     unisparse_ctx *c = new (std::nothrow) unisparse_ctx;
     if (c == nullptr) return UNISPARSE_ERR_HIP;
+    c->scratch = scratch_ptr;
     c->device = device;
     c->n_cu = prop.multiProcessorCount;
     *ctx = c;
@@ -388,6 +403,17 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     pa.n_cu = ctx->n_cu;
     if (launch_proxy_scores(pa, stream) != hipSuccess) return UNISPARSE_ERR_HIP;
     return select_impl(p, s, g, hg, sc, M, stream);
+}
+
+unisparse_status unisparse_build_mask_static(unisparse_ctx *ctx, const unisparse_problem *p,
+                                             const unisparse_select *s, unisparse_tensor Q, unisparse_tensor K,
+                                             uint64_t *M, void *stream)
+{
+    if (ctx == nullptr) return UNISPARSE_ERR_NULL;
+    const size_t need = unisparse_workspace_bytes(p, s);      // 0 for an invalid problem: build_mask reports which
+    if (need > (size_t)UNISPARSE_STATIC_WORKSPACE_BYTES) return UNISPARSE_ERR_WORKSPACE;
+    return unisparse_build_mask(ctx, p, s, Q, K, ctx->scratch, (size_t)UNISPARSE_STATIC_WORKSPACE_BYTES, M, nullptr,
+                                stream);
 }
 
 unisparse_status unisparse_select_blocks(unisparse_ctx *ctx, const unisparse_problem *p, const unisparse_select *s,

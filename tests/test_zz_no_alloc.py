@@ -1,0 +1,42 @@
+"""unisparse_build_mask_static (the entry point for callers that cannot allocate): same mask as
+unisparse_build_mask, bit for bit, on two calls in a row, the second on a smaller problem; too large a
+problem is refused."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_14082_amd import api
+from paper_2512_14082_amd import workloads as W
+
+import parity_utils as PU
+
+pytestmark = pytest.mark.gpu
+
+
+def test_static_workspace_entry_point_matches_build_mask():
+    ctx = api.Context(0)
+    first = W.gqa_planted(L=8192, H=8, Hkv=2, S=128, P=0.9, seed=71)
+    second = W.random_small(H=4, Hkv=2, lengths=(300, 77, 1000), S=128, causal=True, mode=W.TOP_K, param=0.3, seed=72)
+    second.c_q, second.c_k, second.c_h = 16, 4, 2
+    for w in (first, second):
+        q, k, _ = PU.device_tensors(w)
+        p, s = PU.problem_of(w), PU.select_of(w)
+        assert ctx.workspace_bytes(p, s) <= 64 << 20
+        m_ref, _ = ctx.build_mask(p, s, q, k)
+        m = ctx.alloc_mask(p)
+        m.fill_(-1)
+        torch.cuda.synchronize()
+        before = torch.cuda.memory_allocated()
+        ctx.build_mask_static(p, s, q, k, m)
+        assert torch.cuda.memory_allocated() == before
+        torch.cuda.synchronize()
+        assert torch.equal(m, m_ref), w.name
+        assert api.unpack_mask(m, p.n_cols).any(-1).all()
+    # a problem whose workspace exceeds the static one is refused before anything is launched
+    big = api.Problem([0, 131072], 32, 8, 128, True)
+    s = api.Select()
+    assert ctx.workspace_bytes(big, s) > 64 << 20
+    dummy = torch.empty((1, 128, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(api.UnisparseError) as e:
+        ctx.build_mask_static(big, s, dummy, dummy, torch.zeros(8, dtype=torch.int64, device="cuda"))
+    assert e.value.code == 5
