@@ -212,7 +212,8 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int v = 0; v < 16; ++v) oacc[db][v] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
+    float m_run = -INFINITY;                     // reference value of the exponentials (raw logits), per query row
+    float msc = -INFINITY;                       // m_run * c2 + kOff, or -inf while the row has seen no finite logit
     const float c2 = a.scale_log2;
     const int i16 = lane & 15;
     static_assert(C::KB == 2, "the pipeline below works on two 32-key tiles per wavefront and block");
@@ -220,9 +221,19 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     // State is kept twice, indexed by the parity of the sub-step (= t).
     f32x16 sacc[2];                              // S^T tile
     u32x4 pbw[2][2];                             // P^T tile as packed bf16 pairs: two MFMA operands of 16 keys
-    float sm_msc[2], sm_alpha[2], sm_sum[2];     // scaled reference value of the exponentials, rescale factor, row sum
     float sm_a[2][2], sm_x[2][2];                // exponent arguments / exponentials in flight (even, odd value)
-    float sm_ma = -INFINITY, sm_mb = -INFINITY;
+    uint32_t ovf = 0;                            // OR of the packed probabilities of the sub-step in flight
+    // Row sums on the matrix pipe: lacc += R P^T with v_mfma_f32_16x16x32_bf16, where the 16 x 32 matrix R has ones in
+    // row 0 for the contraction indices of lanes 0-15 and 32-47 and in row 1 for those of lanes 16-31 and 48-63.  A lane
+    // of a P^T operand holds eight probabilities of query (lane % 32), so row 0 of the product collects the sixteen
+    // probabilities of queries 0-15 and row 1 those of queries 16-31: lacc[0] / lacc[1] of lanes 0-15.
+    f32x4 lacc = {0.0f, 0.0f, 0.0f, 0.0f};
+    bf16x8 ones_a;
+    {
+        const bool one = (lane & 15) < 2 && ((lane >> 4) & 1) == (lane & 15);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ones_a[e] = one ? (bf16_t)1.0f : (bf16_t)0.0f;
+    }
 
     // ---- operand fetches -------------------------------------------------------------------------------
     // MFMA "units": a QK unit is one MFMA on 32 keys x 16 dims (operand = one 16-byte read of K), a PV unit
@@ -298,110 +309,97 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
         return km;
     };
     auto needs_mask = [&](int j) __attribute__((always_inline)) -> bool { return (CAUSAL && j == i) || j == j_short; };
-    constexpr int NMX = 6;
-    // The two kernels close a sub-step differently (measured: each way is the faster one for its kernel).
-    constexpr bool kLazy = !DENSE;
-    const float lazy_gap = 8.0f / c2;            // 8 binary orders of magnitude, in units of the raw logits
+    // Reference value of the exponentials.  Softmax is shift-invariant, so any reference works as long as no
+    // exponential overflows and the row's largest ones stay far above the underflow threshold.  The reference of a
+    // row is the maximum of the first tile that shows it a finite logit, and from then on it moves only when some
+    // probability would reach 2^(kOff + 1) relative to it; the probabilities carry a constant factor 2^-kOff, which
+    // puts that bound at 2.0: "some value of the tile reached 2.0" is one bit of the bf16 exponent (infinities and
+    // NaNs have it too), read off the OR of the packed probabilities.  The common case therefore needs no row
+    // maximum, no rescaling factor and no rescaling test: per value one fma, one exponential, half a conversion,
+    // and a quarter of an OR.  The row sums are taken by the matrix pipe over the very bf16 values the PV product
+    // multiplies (numerator and denominator round alike).
+    constexpr float kOff = 20.0f;
+    constexpr int NMX = 2;
+    // Starts sub-step `par`: arguments of values 0 and 1, exponential of value 0.
     auto mx_chunk = [&](auto par_c, auto m_c, bf16x8 &next) __attribute__((always_inline)) {
         constexpr int par = decltype(par_c)::value, m = decltype(m_c)::value;
         const f32x16 &s = sacc[par];
         if constexpr (m == 0) {
-            sm_ma = fmaxf(fmaxf(s[0], s[1]), s[2]);
-            sm_mb = fmaxf(fmaxf(s[3], s[4]), s[5]);
-            sm_ma = fmaxf(fmaxf(sm_ma, s[6]), s[7]);
-            asm volatile("" : "+v"(sm_ma), "+v"(sm_mb), "+v"(next));
-        } else if constexpr (m == 1) {
-            sm_mb = fmaxf(fmaxf(sm_mb, s[8]), s[9]);
-            sm_ma = fmaxf(fmaxf(sm_ma, s[10]), s[11]);
-            sm_mb = fmaxf(fmaxf(sm_mb, s[12]), s[13]);
-            sm_ma = fmaxf(fmaxf(sm_ma, s[14]), s[15]);
-            asm volatile("" : "+v"(sm_ma), "+v"(sm_mb), "+v"(next));
-        } else if constexpr (m == 2) {
-            const float mx = fmaxf(sm_ma, sm_mb);
-            auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-            // Sparse kernel: the reference value of the exponentials (m_run) follows the row maximum lazily - it
-            // moves only when the tile's maximum exceeds it by more than 2^8 in the exponent, so probabilities stay
-            // <= 256 (exact after the final division by the row sum) and the rescaling of O^T becomes rare.  Dense
-            // kernel: the reference is the running maximum (its long rows rescale seldom anyway).
-            const float tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-            if constexpr (kLazy) sm_ma = tmax > m_run + lazy_gap ? tmax : m_run;
-            else sm_ma = fmaxf(m_run, tmax);
-            asm volatile("" : "+v"(sm_ma), "+v"(next));
-        } else if constexpr (m == 3) {
-            const float m_safe = sm_ma == -INFINITY ? 0.0f : sm_ma;
-            sm_alpha[par] = (m_run - m_safe) * c2;       // exponent of the rescale factor; the factor itself follows
-            sm_msc[par] = m_safe * c2;
-            m_run = sm_ma;
-            asm volatile("" : "+v"(sm_alpha[par]), "+v"(sm_msc[par]), "+v"(m_run), "+v"(next));
-        } else if constexpr (m == 4) {
-            sm_a[par][0] = fmaf(s[0], c2, -sm_msc[par]);
-            sm_a[par][1] = fmaf(s[1], c2, -sm_msc[par]);
-            sm_alpha[par] = fast_exp2(sm_alpha[par]);    // (needed only when the sub-step closes)
-            if constexpr (kLazy) {
-                asm volatile("" : "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(sm_alpha[par]), "+v"(next));
-            } else {
-                sm_sum[par] = 0.0f;
-                asm volatile("" : "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(sm_alpha[par]), "+v"(sm_sum[par]), "+v"(next));
-            }
+            sm_a[par][0] = fmaf(s[0], c2, -msc);
+            sm_a[par][1] = fmaf(s[1], c2, -msc);
+            asm volatile("" : "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
         } else {
             sm_x[par][0] = fast_exp2(sm_a[par][0]);
             asm volatile("" : "+v"(sm_x[par][0]), "+v"(next));
         }
     };
-    // EX chunk of value u: [pack values u-1, u to bf16]; (dense kernel: row sum += exp(u);) exp(u+1); argument(u+2).
+    // EX chunk of value u: [pack values u-1, u to bf16, OR into ovf]; exp(u+1); argument(u+2).
     auto ex_chunk = [&](auto par_c, auto u_c, bf16x8 &next) __attribute__((always_inline)) {
         constexpr int par = decltype(par_c)::value, u = decltype(u_c)::value;
         if constexpr ((u & 1) != 0) {
             f32x2 pe = {sm_x[par][0], sm_x[par][1]};
             pbw[par][u >> 3][(u >> 1) & 3] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pe, bf16x2));
         }
-        if constexpr (!kLazy) sm_sum[par] += sm_x[par][u & 1];
+        if constexpr (u == 3) ovf = pbw[par][0][0] | pbw[par][0][1];
+        if constexpr (u == 7) ovf = ovf | pbw[par][0][2] | pbw[par][0][3];
+        if constexpr (u == 11) ovf = ovf | pbw[par][1][0] | pbw[par][1][1];
+        if constexpr (u == 15) ovf = ovf | pbw[par][1][2] | pbw[par][1][3];
         if constexpr (u + 1 < 16) sm_x[par][(u + 1) & 1] = fast_exp2(sm_a[par][(u + 1) & 1]);
-        if constexpr (u + 2 < 16) sm_a[par][u & 1] = fmaf(sacc[par][u + 2], c2, -sm_msc[par]);
+        if constexpr (u + 2 < 16) sm_a[par][u & 1] = fmaf(sacc[par][u + 2], c2, -msc);
         // (only values that exist take part in a pin: a pinned constant would cost a move)
-        if constexpr (kLazy) {
-            if constexpr ((u & 1) != 0) {
-                asm volatile("" : "+v"(pbw[par][u >> 3][(u >> 1) & 3]), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]),
-                                  "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
-            } else {
-                asm volatile("" : "+v"(sm_x[par][0]), "+v"(sm_x[par][1]), "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
-            }
+        if constexpr ((u & 3) == 3) {
+            asm volatile("" : "+v"(pbw[par][u >> 3][(u >> 1) & 3]), "+v"(ovf), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]),
+                              "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
+        } else if constexpr ((u & 1) != 0) {
+            asm volatile("" : "+v"(pbw[par][u >> 3][(u >> 1) & 3]), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]),
+                              "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
         } else {
-            if constexpr ((u & 1) != 0) {
-                asm volatile("" : "+v"(pbw[par][u >> 3][(u >> 1) & 3]), "+v"(sm_sum[par]), "+v"(sm_x[par][0]),
-                                  "+v"(sm_x[par][1]), "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
-            } else {
-                asm volatile("" : "+v"(sm_sum[par]), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]), "+v"(sm_a[par][0]),
-                                  "+v"(sm_a[par][1]), "+v"(next));
-            }
+            asm volatile("" : "+v"(sm_x[par][0]), "+v"(sm_x[par][1]), "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
         }
     };
-    // Closes sub-step `par`.  Sparse kernel: the row sum is taken here, in one piece beside the other wavefront's
-    // MFMAs, over the bf16-rounded probabilities just packed - the very values the PV product multiplies, so that
-    // the rounding cancels between numerator and denominator (with a lazy reference the largest probability of a
-    // row is no longer an exact 1; a row dominated by one key still returns that key's V exactly).  Dense kernel:
-    // the sum of the unrounded values was kept along the chain.  O^T (which holds the products up to the sub-step
-    // before) is rescaled when a reference value moved.
-    auto sm_finish = [&](auto par_c) __attribute__((always_inline)) {
+    // The uncommon case, and the first tile of every row: take the tile's row maximum (one exchange with the other
+    // half of the key rows, lane ^ 32), move the reference of the rows that exceed it, redo the tile's probabilities
+    // and rescale what was accumulated under the old reference.  `started` says whether the next sub-step (the other
+    // parity) has already taken its first values under the old reference; they are redone as well.
+    auto sm_slow = [&](auto par_c, auto started_c) __attribute__((always_inline)) {
         constexpr int par = decltype(par_c)::value;
-        if constexpr (kLazy) {
-            float lo[2] = {0.0f, 0.0f}, hi[2] = {0.0f, 0.0f};
+        constexpr bool started = decltype(started_c)::value != 0;
+        const f32x16 &s = sacc[par];
+        float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
 #pragma unroll
-            for (int g = 0; g < 2; ++g)
+        for (int v = 3; v < 16; ++v) mx = fmaxf(mx, s[v]);
+        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        const float tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        const float m_new = fmaxf(m_run, tmax);
+        const bool none = m_new == -INFINITY;                 // the row has still seen nothing but masked keys
+        const float m_safe = none ? 0.0f : m_new;
+        const float alpha = fast_exp2((m_run - m_safe) * c2); // 1 for rows whose reference stays, 0 for a first reference
+        m_run = m_new;
+        msc = none ? -INFINITY : fmaf(m_safe, c2, kOff);
+        const float msc_safe = none ? 0.0f : msc;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    lo[g] += __uint_as_float(pbw[par][g][e] << 16);
-                    hi[g] += __uint_as_float(pbw[par][g][e] & 0xffff0000u);
-                }
-            sm_sum[par] = (lo[0] + hi[0]) + (lo[1] + hi[1]);
+        for (int v = 0; v < 16; v += 2) {
+            f32x2 pe = {fast_exp2(fmaf(s[v], c2, -msc_safe)), fast_exp2(fmaf(s[v + 1], c2, -msc_safe))};
+            pbw[par][v >> 3][(v >> 1) & 3] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pe, bf16x2));
         }
-        l_run = fmaf(l_run, sm_alpha[par], sm_sum[par]);
-        if (__any(sm_alpha[par] != 1.0f)) {
+        if (__any(alpha != 1.0f)) {
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) oacc[db][v] *= sm_alpha[par];
+                for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+            lacc[0] *= __shfl(alpha, lane & 15, 64);
+            lacc[1] *= __shfl(alpha, (lane & 15) + 16, 64);
         }
+        if constexpr (started) {
+            sm_a[par ^ 1][0] = fmaf(sacc[par ^ 1][0], c2, -msc);
+            sm_a[par ^ 1][1] = fmaf(sacc[par ^ 1][1], c2, -msc);
+            sm_x[par ^ 1][0] = fast_exp2(sm_a[par ^ 1][0]);
+        }
+    };
+    // Closes sub-step `par`: nothing to do unless some probability reached 2.0 (or is not a number: a row without a
+    // reference yet).
+    auto sm_finish = [&](auto par_c, auto started_c) __attribute__((always_inline)) {
+        if (__any((ovf & 0x40004000u) != 0u)) sm_slow(par_c, started_c);
     };
     const std::integral_constant<int, 0> c0;
     const std::integral_constant<int, 1> c1;
@@ -442,6 +440,8 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
             } else {
                 constexpr int g = (w & 7) >> 2, db = w & 3;
                 oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, __builtin_bit_cast(bf16x8, pbw[t][g]), oacc[db], 0, 0, 0);
+                if constexpr (db == 3)
+                    lacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones_a, __builtin_bit_cast(bf16x8, pbw[t][g]), lacc, 0, 0, 0);
             }
             if constexpr (w + kAhead < n_all) opnd[(w + kAhead) % kAhead] = fetch(std::integral_constant<int, (w + kAhead < n_all ? w + kAhead : 0)>{});
             // block loads, evenly spread
@@ -467,11 +467,11 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
                 if constexpr (w >= 25 && w < 25 + NMX) mx_chunk(c1, std::integral_constant<int, (w >= 25 && w < 25 + NMX ? w - 25 : 0)>{}, next);
                 if constexpr (w == 15) {
                     __builtin_amdgcn_sched_barrier(0);
-                    sm_finish(c1);
+                    sm_finish(c1, c1);
                 }
                 if constexpr (w == 31) {
                     __builtin_amdgcn_sched_barrier(0);
-                    sm_finish(c0);
+                    sm_finish(c0, c1);
                 }
             } else {
                 if constexpr (w < 8) {
@@ -480,7 +480,7 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
                 }
                 if constexpr (w == 7) {
                     __builtin_amdgcn_sched_barrier(0);
-                    sm_finish(c1);
+                    sm_finish(c1, c0);
                 }
             }
         });
@@ -521,9 +521,7 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
             sm_mask(c0, km);
             sm_mask(c1, km);
         }
-        static_for<NMX>([&](auto m_c) __attribute__((always_inline)) { mx_chunk(c0, m_c, opnd[0]); });
-        static_for<16>([&](auto u_c) __attribute__((always_inline)) { ex_chunk(c0, u_c, opnd[0]); });
-        sm_finish(c0);
+        sm_slow(c0, c0);
         static_for<NMX>([&](auto m_c) __attribute__((always_inline)) { mx_chunk(c1, m_c, opnd[0]); });
         flip_k();                                 // block 1's K is in buffer 1
         __syncthreads();                          // K buffer 0 is reloaded from the first iteration on
@@ -554,7 +552,9 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
     __syncthreads();
 
     // ---- merge the two key halves through LDS, normalise, store -------------------------------------
-    l_run += swap_half(l_run);
+    // row sums: lanes 0-15 hold those of queries 0-15 in lacc[0] and of queries 16-31 in lacc[1]
+    const float l_lo = __shfl(lacc[0], lane & 15, 64), l_hi = __shfl(lacc[1], lane & 15, 64);   // (all lanes active)
+    const float l_run = lr < 16 ? l_lo : l_hi;
     float *mo = reinterpret_cast<float *>(lds) + qq * (66 * 64);      // [64 + 2 slots][64 lanes] per query slice
     float *ml = mo + 64 * 64;
     if (kh == 1) {
@@ -596,7 +596,7 @@ __global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(
             }
         }
         if (a.lse != nullptr && lh == 0 && row_exists)
-            a.lse[(int64_t)head * a.total_tokens + tok] = empty ? -INFINITY : (__log2f(l_t) + m_t * c2) * kLn2;
+            a.lse[(int64_t)head * a.total_tokens + tok] = empty ? -INFINITY : (__log2f(l_t) + m_t * c2 + kOff) * kLn2;
     }
 }
 

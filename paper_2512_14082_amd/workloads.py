@@ -314,6 +314,50 @@ def random_small(H: int = 4, Hkv: int = 2, lengths: Sequence[int] = (256,), S: i
                     gain=0.0, seed=seed)
 
 
+def steep_logits(kind: str = "rising", H: int = 2, Hkv: int = 1, lengths: Sequence[int] = (1024,), S: int = 128,
+                 causal: bool = True, step: float = 16.0, seed: int = 77, d: int = HEAD_DIM) -> Workload:
+    """Inputs whose attention logits span hundreds of natural-log units inside one row: the case in which a streaming
+    softmax has to move its reference value again and again (or sees later terms vanish against it).
+
+    Queries are N(0,1) + 6 u for a unit vector u, keys are 0.5 N(0,1) + b u with the key's boost b chosen so that the
+    logit q.k / sqrt(d) is about `step` * level: "rising": level = key-block index (every block dwarfs the ones before
+    it); "falling": level = -(key-block index); "spikes": level 0 except for 2 % of the keys, which get a random level in
+    [1, 12] (a new maximum in the middle of a tile, at random places); "ramp": level grows by 1/8 per key inside
+    every block and restarts (a new maximum in nearly every 32-key tile)."""
+    rng = np.random.default_rng(seed)
+    cu = [0]
+    for L in lengths:
+        cu.append(cu[-1] + int(L))
+    T = cu[-1]
+    u = _unit(rng, d).astype(np.float32)
+    q = rng.standard_normal((H, T, d), dtype=np.float32) + 6.0 * u
+    k = 0.5 * rng.standard_normal((Hkv, T, d), dtype=np.float32)
+    v = rng.standard_normal((Hkv, T, d), dtype=np.float32)
+    level = np.zeros((Hkv, T), np.float32)
+    for b in range(len(lengths)):
+        pos = np.arange(cu[b + 1] - cu[b])
+        if kind == "rising":
+            lv = (pos // S).astype(np.float32)
+        elif kind == "falling":
+            lv = -(pos // S).astype(np.float32)
+        elif kind == "ramp":
+            lv = (pos % S).astype(np.float32) / 8.0
+        elif kind == "spikes":
+            lv = None
+        else:
+            raise ValueError(kind)
+        for g in range(Hkv):
+            if lv is None:
+                x = np.where(rng.random(len(pos)) < 0.02, rng.integers(1, 13, len(pos)), 0).astype(np.float32)
+            else:
+                x = lv
+            level[g, cu[b]:cu[b + 1]] = x
+    boost = level * np.float32(step * np.sqrt(d) / 6.0)
+    k += boost[..., None] * u
+    return Workload(f"steep_{kind}_T{T}", f32_to_bf16_bits(q), f32_to_bf16_bits(k), f32_to_bf16_bits(v), cu, S, causal,
+                    mode=TOP_K, param=0.5, gain=0.0, seed=seed)
+
+
 def random_32k(d: int = HEAD_DIM, seed: int = BASE_SEED + 9, **_unused) -> Workload:
     """GQA 32/8 layer at L = 32K with i.i.d. Gaussian tensors and a fixed 25 % budget: the timing shape for the
     head dimensions other than 128 (no planted structure; selection at a fixed budget keeps the density known)."""

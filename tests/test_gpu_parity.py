@@ -78,6 +78,38 @@ def test_dense_attention_any_length(ctx, oracle):
     np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=1e-3, atol=2e-3)
 
 
+@pytest.mark.parametrize("kind", ["rising", "falling", "spikes", "ramp"])
+@pytest.mark.parametrize("S,causal", [(128, True), (128, False), (64, True)])
+def test_attention_with_logits_spanning_hundreds_of_units(ctx, oracle, kind, S, causal):
+    """Rows whose logits differ by up to ~190 natural-log units: the attention kernels keep one reference value per
+    row for their exponentials and move it only when a probability would grow past a bound, so these inputs drive
+    that path (a new reference in every block, in the middle of tiles, in nearly every tile) and its opposite (terms
+    that vanish against an early reference).  Dense and block-sparse (random half of the blocks) against the oracle,
+    ragged last block included."""
+    w = W.steep_logits(kind, H=2, Hkv=1, lengths=(8 * S + 40, 3 * S), S=S, causal=causal, seed=70 + S)
+    q, k, v = PU.device_tensors(w)
+    qf, kf, vf = w.f32()
+    p = PU.problem_of(w)
+    o, lse = ctx.full_attn(p, q, k, v, want_lse=True)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, S, causal, None)
+    PU.check_output(o.float().cpu().numpy(), o_ref, f"dense {kind}")
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=1e-3, atol=2e-3)
+    rng = np.random.default_rng(5)
+    nq, nk = p.n_rows, p.n_cols
+    m = (rng.random((2, nq, nk)) < 0.5).astype(np.uint8)
+    loc, nb = PU.row_geometry(w.cu_seqlens, S)
+    m[:, np.arange(nq), loc] = 1                                   # keep the diagonal so that no row is empty
+    if causal:
+        m &= (np.arange(nk)[None, :] <= loc[:, None]).astype(np.uint8)[None]
+    m &= (np.arange(nk)[None, :] < nb[:, None]).astype(np.uint8)[None]
+    o, lse = ctx.sparse_attn(p, q, k, v, api.pack_mask(m), want_lse=True)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.masked_attention(qf, kf, vf, w.cu_seqlens, S, causal, m)
+    PU.check_output(o.float().cpu().numpy(), o_ref, f"sparse {kind}")
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=1e-3, atol=2e-3)
+
+
 def test_planted_gqa_4k(ctx, oracle):
     w = W.gqa_planted(L=4096, H=8, Hkv=2, S=128, P=0.95, seed=21)
     PU.full_pipeline_check(ctx, oracle, w)
