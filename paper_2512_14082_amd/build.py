@@ -11,8 +11,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libunisparse.so")
-SOURCES = ["attention.hip", "proxy.hip", "proxy_d64.hip", "proxy_d256.hip", "attention_generic.hip", "pool.hip",
-           "select.hip", "capi.hip"]
+SOURCES = ["attention_d256.hip", "attention.hip", "attention_d64.hip", "proxy.hip", "proxy_d64.hip", "proxy_d256.hip",
+           "pool.hip", "select.hip", "capi.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,

@@ -1,636 +1,17 @@
-// Block-sparse attention (Alg. 1 step 5, Sec. 2.2) and the dense baseline (Sec. 2.1), one kernel.
-//
-// A workgroup owns one (query head, query block of S rows) and visits the key blocks its mask row
-// selects (or every valid block when dense).  K and V blocks go from global memory straight into
-// LDS (global_load_lds_dwordx4, no staging registers), double buffered: the next block's loads
-// are in flight during the current block's math and are awaited at the single barrier per block.
-//
-// Wavefront tiling: wavefront (qq, kh) owns query rows [32 qq, 32 qq + 32) and key rows [64 kh, 64 kh + 64)
-// of every visited block, with its own running max / sum / output; the key groups are merged through LDS
-// once, after the last block.  S = 128: eight wavefronts (two per SIMD); S = 64: two wavefronts.
-//
-// Every wavefront runs the same software pipeline over "sub-steps" of 32 keys: while the matrix pipe works
-// on S^T of sub-step s+1 and on the PV product of sub-step s-1, the VALU does the softmax of sub-step s, cut
-// into chunks of about four instructions that sit between consecutive MFMAs (an MFMA hides that much VALU
-// work of the same or the other wavefront of the SIMD; measured on gfx950, where dot-product and long runs
-// of transcendental instructions are the ones that do not hide).
-//
-// All matrix products are computed transposed so that a lane owns whole query rows:
-//   S^T (keys x queries)  = K Q^T   : A = K rows from LDS (16-byte reads), B = Q^T kept in registers
-//   O^T (dims x queries) += V^T P^T : A = V^T via the LDS transpose read of row-major V,
-//                                     B = P^T, which is exactly the accumulator layout of S^T
-// With v_mfma_f32_32x32x16_bf16 a lane holds column (query) lane % 32 of the accumulator, so row max,
-// row sum and the rescale of O^T are lane-local; only one exchange with lane ^ 32 is needed.
-//
-// LDS layout: rows of 256 bytes, unpadded (a direct-to-LDS load writes 64 lanes x 16 bytes
-// contiguously), with the 16-byte chunk index XOR-swizzled by the row so that the K operand reads
-// (32 rows, same column) and the V transpose reads (8 rows x 64 bytes) spread over all banks.  The
-// swizzle is applied by choosing which global chunk each lane fetches.
-#include "common.h"
+// Launcher of the attention kernel (attention_kernel.h) and its head-dimension-128 instantiations.
+#include "attention_kernel.h"
 
 namespace us {
 
-template <int S>
-struct AttnCfg {
-    static constexpr int QW = S / 32;            // query slices of 32 rows
-    static constexpr int KW = S / 64;            // key groups of 64 rows
-    static constexpr int NW = QW * KW;
-    static constexpr int NT = NW * 64;
-    static constexpr int KC = S / KW;            // keys per wavefront per block
-    static constexpr int KB = KC / 32;           // 32-key MFMA tiles per wavefront per block
-    static constexpr int kTileBytes = S * 256;   // one K or V block
-    static constexpr int kStageBytes = 2 * kTileBytes;
-    static constexpr int kLdsBytes = 2 * kStageBytes;
-    static constexpr int kDma = S / 4 / NW;      // 1 KB direct-to-LDS loads per wavefront per K (or V) block
-};
-
-__device__ __forceinline__ int k_swizzle(int row) { return row & 15; }
-__device__ __forceinline__ int v_swizzle(int row) { return (row & 3) << 2; }
-
-// Work order.  The hardware deals workgroup ids round-robin to the 8 XCDs (private L2 each), and each
-// XCD works through its share in order.  Workgroups are grouped in chunks of (HG query heads of one key
-// head) x (R consecutive query-block rows), 32 workgroups that read the same K/V; chunk number ci runs on
-// XCD ci % 8, longest rows first, and the head group is rotated against the row group so that every XCD
-// sees every head (masks of different heads have different densities).
-struct AttnOrder {
-    int R;           // rows per chunk
-    int HG;          // query heads (of one key head) per chunk
-    int n_rg;        // row groups = ceil(NQ / R)
-    int n_chunks;    // n_rg * (n_heads_q / HG)
-    int head_major;  // 1: all row groups of key head 0, then head 1, ... ; 0: row groups outermost, heads rotated
-};
-
-template <int S, bool CAUSAL, bool DENSE>
-__global__ __launch_bounds__(AttnCfg<S>::NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attention_kernel(AttnArgs a, AttnOrder ord)
-{
-    using C = AttnCfg<S>;
-    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-    __shared__ uint16_t jlist[UNISPARSE_MAX_BLOCKS_PER_SEQ];
-    __shared__ int jcount;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lr = lane & 31, lh = lane >> 5;
-    const int qq = wave % C::QW, kh = wave / C::QW;
-
-    // ---- which (head, query-block row) ---------------------------------------------------------------
-    const int G = a.n_heads_q / a.n_heads_kv;
-    const int cs = ord.R * ord.HG;
-    const int xcd = blockIdx.x % kNumXcd, idx = blockIdx.x / kNumXcd;
-    const int ci = (idx / cs) * kNumXcd + xcd;
-    if (ci >= ord.n_chunks) return;
-    const int slot = idx % cs;
-    const int n_hg = a.n_heads_q / ord.HG;                   // head groups
-    const int rg = ord.head_major ? ci % ord.n_rg : ci / n_hg;
-    const int hg = ord.head_major ? ci / ord.n_rg : (ci % n_hg + rg) % n_hg;
-    // consecutive workgroups of an XCD go to different shader engines: vary the row, not the head, fastest,
-    // so that no engine collects all workgroups of a dense (or sparse) head
-    const int row = a.NQ - 1 - (rg * ord.R + slot % ord.R);
-    if (row < 0) return;
-    const int head = hg * ord.HG + slot / ord.R;
-    const int kvh = head / G;
-    int seq, i, nb;
-    locate_row(a.st, S, row, seq, i, nb);
-    const int64_t tok0 = a.st.cu_tok[seq];
-    const int Lb = a.st.cu_tok[seq + 1] - a.st.cu_tok[seq];
-    // A sequence whose length is not a multiple of S ends in a shorter block: its missing rows are never
-    // loaded (row indices are clamped to the sequence), never attended (masked like the future keys of the
-    // diagonal block) and never stored.
-    const int j_short = Lb % S != 0 ? nb - 1 : -1;         // index of the shorter last block, if any
-    const int rows_short = Lb % S;                          // its number of rows
-    const int q_rows = i == j_short ? rows_short : S;       // query rows of this workgroup that exist
-    const int nvalid = CAUSAL ? i + 1 : nb;
-
-    // The selected key blocks of this row, expanded once from the mask bits into an ascending list in LDS
-    // (one mask word per lane of wavefront 0, positions placed by a prefix sum of the popcounts).
-    int n_sel = nvalid;
-    if (!DENSE) {
-        if (wave == 0) {
-            const int nw = (nvalid + 63) / 64;
-            uint64_t bits = 0;
-            if (lane < nw) {
-                bits = a.mask[((int64_t)head * a.NQ + row) * a.W + lane];
-                const int hi = nvalid - lane * 64;
-                if (hi < 64) bits &= (1ull << hi) - 1ull;
-            }
-            const int cnt = __builtin_popcountll(bits);
-            int incl = cnt;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int up = __shfl_up(incl, off, 64);
-                if (lane >= off) incl += up;
-            }
-            int pos = incl - cnt;
-            while (bits != 0) {
-                jlist[pos++] = (uint16_t)(lane * 64 + __builtin_ctzll(bits));
-                bits &= bits - 1;
-            }
-            if (lane == 63) jcount = incl;
-        }
-        __syncthreads();
-        n_sel = __builtin_amdgcn_readfirstlane(jcount);
-    }
-    int cursor = 0;
-    auto next_block = [&]() __attribute__((always_inline)) -> int {
-        if (cursor >= n_sel) return -1;
-        const int j = DENSE ? cursor : __builtin_amdgcn_readfirstlane((int)jlist[cursor]);
-        ++cursor;
-        return j;
-    };
-
-    // ---- this wavefront's 32 query rows as B operands -------------------------------------------------
-    bf16x8 qreg[8];
-    {
-        const int qr = 32 * qq + lr < q_rows ? 32 * qq + lr : q_rows - 1;
-        const bf16_t *src = a.q.ptr + (tok0 + (int64_t)i * S + qr) * a.q.stride_tok +
-                            (int64_t)head * a.q.stride_head + 8 * lh;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
-    }
-
-    // ---- direct-to-LDS block loads: lane l of a 1 KB load fills row l / 16, physical chunk l % 16 -----
-    // Issued as inline assembly so that the compiler does not serialise later LDS reads behind them; their
-    // completion is awaited explicitly (vmcnt) before the barrier that publishes the buffer.
-    const bf16_t *kptr = a.k.ptr + (int64_t)kvh * a.k.stride_head + tok0 * a.k.stride_tok;
-    const bf16_t *vptr = a.v.ptr + (int64_t)kvh * a.v.stride_head + tok0 * a.v.stride_tok;
-    const int dma_row = lane >> 4, dma_chunk = lane & 15;
-    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
-    auto dma16 = [](const void *gbase, uint32_t goff, uint32_t lds_addr) __attribute__((always_inline)) {
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
-                     :
-                     : "s"(gbase), "v"(goff), "s"(lds_addr)
-                     : "memory", "m0");
-    };
-    // Every wavefront issues kDma instructions of 1 KB (4 rows) for K and as many for V per block.
-    constexpr int kDma = C::kDma;
-    // Per-lane byte offset of this lane's 16 bytes inside a block (row r, swizzled chunk) for the wavefront's
-    // first load; load number d of a block is 4 * NW rows further and that distance goes into the wave-uniform
-    // base address.  The K swizzle has a period of 16 rows: with 4 * NW = 8 the odd loads need an offset of
-    // their own (the V swizzle has a period of 4 rows).
-    constexpr int NKO = (4 * C::NW) % 16 == 0 ? 1 : 2;
-    uint32_t koff[NKO], voff0;
-    {
-        const int r = 4 * wave + dma_row;
-#pragma unroll
-        for (int o = 0; o < NKO; ++o)
-            koff[o] = (uint32_t)(r * a.k.stride_tok + (dma_chunk ^ k_swizzle(r + 4 * C::NW * o)) * 8) * 2u;
-        voff0 = (uint32_t)(r * a.v.stride_tok + (dma_chunk ^ v_swizzle(r)) * 8) * 2u;
-    }
-    // LDS map: K buffers at [0, 2 tiles), V buffers at [2 tiles, 4 tiles).  Instruction d of a block pair:
-    // d < kDma loads K rows of block jk into K buffer bk, d >= kDma loads V rows of block jv into V buffer bv.
-    const int64_t k_step = (int64_t)4 * C::NW * a.k.stride_tok, v_step = (int64_t)4 * C::NW * a.v.stride_tok;
-    const uint32_t lds_wave = lds_base + wave * 1024;
-    auto dma_one = [&](int d, int jk, int bk, int jv, int bv) __attribute__((always_inline)) {
-        if (d < kDma) {
-            dma16(kptr + (int64_t)jk * S * a.k.stride_tok + d * k_step, koff[d % NKO],
-                  lds_wave + bk * C::kTileBytes + d * C::NW * 1024);
-        } else {
-            const int e = d - kDma;
-            dma16(vptr + (int64_t)jv * S * a.v.stride_tok + e * v_step, voff0,
-                  lds_wave + (2 + bv) * C::kTileBytes + e * C::NW * 1024);
-        }
-    };
-
-    // The same loads for a block that may be the shorter last one: rows beyond the sequence are replaced by its
-    // last row (only used outside the main loop, so the extra address arithmetic does not matter).
-    auto dma_clamped = [&](int d, int jk, int bk, int jv, int bv) __attribute__((always_inline)) {
-        const bool is_k = d < kDma;
-        const int e = is_k ? d : d - kDma, j = is_k ? jk : jv;
-        const int rows = j == j_short ? rows_short : S;
-        int r = 4 * (e * C::NW + wave) + dma_row;
-        const int swz = is_k ? k_swizzle(r) : v_swizzle(r);
-        r = r < rows ? r : rows - 1;
-        const int64_t st = is_k ? a.k.stride_tok : a.v.stride_tok;
-        const uint32_t off = (uint32_t)(r * st + (dma_chunk ^ swz) * 8) * 2u;
-        dma16((is_k ? kptr : vptr) + (int64_t)j * S * st, off,
-              lds_wave + (is_k ? bk : 2 + bv) * C::kTileBytes + e * C::NW * 1024);
-    };
-
-    f32x16 oacc[4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[db][v] = 0.0f;
-    float m_run = -INFINITY;                     // reference value of the exponentials (raw logits), per query row
-    float msc = -INFINITY;                       // m_run * c2 + kOff, or -inf while the row has seen no finite logit
-    const float c2 = a.scale_log2;
-    const int i16 = lane & 15;
-    static_assert(C::KB == 2, "the pipeline below works on two 32-key tiles per wavefront and block");
-    // The unit of the software pipeline is a "sub-step": one 32-key tile t of one block, numbered 2 n + t.
-    // State is kept twice, indexed by the parity of the sub-step (= t).
-    f32x16 sacc[2];                              // S^T tile
-    u32x4 pbw[2][2];                             // P^T tile as packed bf16 pairs: two MFMA operands of 16 keys
-    float sm_a[2][2], sm_x[2][2];                // exponent arguments / exponentials in flight (even, odd value)
-    uint32_t ovf = 0;                            // OR of the packed probabilities of the sub-step in flight
-    // Row sums on the matrix pipe: lacc += R P^T with v_mfma_f32_16x16x32_bf16, where the 16 x 32 matrix R has ones in
-    // row 0 for the contraction indices of lanes 0-15 and 32-47 and in row 1 for those of lanes 16-31 and 48-63.  A lane
-    // of a P^T operand holds eight probabilities of query (lane % 32), so row 0 of the product collects the sixteen
-    // probabilities of queries 0-15 and row 1 those of queries 16-31: lacc[0] / lacc[1] of lanes 0-15.
-    f32x4 lacc = {0.0f, 0.0f, 0.0f, 0.0f};
-    bf16x8 ones_a;
-    {
-        const bool one = (lane & 15) < 2 && ((lane >> 4) & 1) == (lane & 15);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) ones_a[e] = one ? (bf16_t)1.0f : (bf16_t)0.0f;
-    }
-
-    // ---- operand fetches -------------------------------------------------------------------------------
-    // MFMA "units": a QK unit is one MFMA on 32 keys x 16 dims (operand = one 16-byte read of K), a PV unit
-    // one MFMA on 16 keys x 32 dims (operand = two transpose reads of V).  Operand reads run kAhead units
-    // in front of the MFMA that consumes them.
-    constexpr int kAhead = 8;
-    constexpr int kDmaGap = 2;                   // MFMA units between two block loads (when the chain is long enough)
-    bf16x8 opnd[kAhead];                          // operand ring
-    // Lane-constant LDS addresses of the operand reads, computed once; every read is "register + immediate".
-    typedef const unsigned char __attribute__((address_space(3))) * lds_ptr;
-    typedef short4v __attribute__((address_space(3))) * lds_s4_ptr;
-    typedef const bf16x8 __attribute__((address_space(3))) * lds_b8_ptr;
-    lds_ptr kaddr[8], vaddr[4];
-    {
-        lds_ptr lbase = (lds_ptr)lds;
-        const int r = C::KC * kh + lr;                                    // K row of tile t = 0 (t adds 32 rows)
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) kaddr[ks] = lbase + (r * 256 + (((2 * ks + lh) ^ k_swizzle(r)) << 4));
-        const int r0 = C::KC * kh + 4 * lh + (i16 >> 2);                  // V row of group g = 0 (g adds 16 rows)
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            const int chunk = (4 * db + 2 * (lr >> 4) + ((i16 & 3) >> 1)) ^ v_swizzle(r0);
-            vaddr[db] = lbase + (2 * C::kTileBytes + r0 * 256 + (i16 & 1) * 8 + (chunk << 4));
-        }
-    }
-    // PV operand: tile t, group g (16 keys) of the tile, dims block db
-    auto v_fetch = [&](int t, int g, int db) __attribute__((always_inline)) -> bf16x8 {
-        lds_ptr p0 = vaddr[db] + (32 * t + 16 * g) * 256;
-        short4v x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)p0);
-        short4v x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(p0 + 8 * 256));
-        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7));
-    };
-    // QK operand: tile t, k-step ks
-    auto k_fetch = [&](int t, int ks) __attribute__((always_inline)) -> bf16x8 {
-        return *(lds_b8_ptr)(kaddr[ks] + 32 * t * 256);
-    };
-    // kaddr / vaddr point into buffer 0 or 1; the other buffer is one block further or back
-    int k_flip = C::kTileBytes, v_flip = C::kTileBytes;
-    auto flip_k = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) kaddr[ks] += k_flip;
-        k_flip = -k_flip;
-    };
-    auto flip_v = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int db = 0; db < 4; ++db) vaddr[db] += v_flip;
-        v_flip = -v_flip;
-    };
-
-    // ---- online softmax in chunks of a few instructions (lane-local per query row) -----------------------
-    // Per sub-step the 16 values of a lane go through
-    //   MX: row maximum, exchange with the other half of the key rows (lane ^ 32), reference value of the
-    //       exponentials, rescale factor; also starts the pipeline below (arguments of values 0 and 1,
-    //       exponential of value 0)
-    //   EX: one chunk per value u: [pack values u-1, u to bf16]; exp(u+1); argument(u+2)
-    //       - nothing in a chunk uses a result of the same chunk, so VALU latency never stalls the wavefront
-    //   and the row sum, taken from the packed values when the sub-step closes.
-    // Every chunk is tied (empty asm) to the operand of the MFMA that follows it, which keeps it between the
-    // same two MFMAs in the machine code: the matrix pipe hides a handful of VALU instructions per MFMA.
-    // Last visited block only: keys after the query's own position (diagonal block of a causal row) and keys
-    // beyond the end of the sequence (shorter last block) are excluded.  key_max = highest admissible key row.
-    auto sm_mask = [&](auto par_c, int key_max) __attribute__((always_inline)) {
-        constexpr int par = decltype(par_c)::value;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            int key = C::KC * kh + 32 * par + 8 * (v >> 2) + 4 * lh + (v & 3);
-            sacc[par][v] = key <= key_max ? sacc[par][v] : -INFINITY;
-        }
-    };
-    auto key_max_of = [&](int j) __attribute__((always_inline)) -> int {
-        int km = j == j_short ? rows_short - 1 : S - 1;
-        if (CAUSAL && j == i) km = min(km, 32 * qq + lr);
-        return km;
-    };
-    auto needs_mask = [&](int j) __attribute__((always_inline)) -> bool { return (CAUSAL && j == i) || j == j_short; };
-    // Reference value of the exponentials.  Softmax is shift-invariant, so any reference works as long as no
-    // exponential overflows and the row's largest ones stay far above the underflow threshold.  The reference of a
-    // row is the maximum of the first tile that shows it a finite logit, and from then on it moves only when some
-    // probability would reach 2^(kOff + 1) relative to it; the probabilities carry a constant factor 2^-kOff, which
-    // puts that bound at 2.0: "some value of the tile reached 2.0" is one bit of the bf16 exponent (infinities and
-    // NaNs have it too), read off the OR of the packed probabilities.  The common case therefore needs no row
-    // maximum, no rescaling factor and no rescaling test: per value one fma, one exponential, half a conversion,
-    // and a quarter of an OR.  The row sums are taken by the matrix pipe over the very bf16 values the PV product
-    // multiplies (numerator and denominator round alike).
-    constexpr float kOff = 20.0f;
-    constexpr int NMX = 2;
-    // Starts sub-step `par`: arguments of values 0 and 1, exponential of value 0.
-    auto mx_chunk = [&](auto par_c, auto m_c, bf16x8 &next) __attribute__((always_inline)) {
-        constexpr int par = decltype(par_c)::value, m = decltype(m_c)::value;
-        const f32x16 &s = sacc[par];
-        if constexpr (m == 0) {
-            sm_a[par][0] = fmaf(s[0], c2, -msc);
-            sm_a[par][1] = fmaf(s[1], c2, -msc);
-            asm volatile("" : "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
-        } else {
-            sm_x[par][0] = fast_exp2(sm_a[par][0]);
-            asm volatile("" : "+v"(sm_x[par][0]), "+v"(next));
-        }
-    };
-    // EX chunk of value u: [pack values u-1, u to bf16, OR into ovf]; exp(u+1); argument(u+2).
-    auto ex_chunk = [&](auto par_c, auto u_c, bf16x8 &next) __attribute__((always_inline)) {
-        constexpr int par = decltype(par_c)::value, u = decltype(u_c)::value;
-        if constexpr ((u & 1) != 0) {
-            f32x2 pe = {sm_x[par][0], sm_x[par][1]};
-            pbw[par][u >> 3][(u >> 1) & 3] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pe, bf16x2));
-        }
-        if constexpr (u == 3) ovf = pbw[par][0][0] | pbw[par][0][1];
-        if constexpr (u == 7) ovf = ovf | pbw[par][0][2] | pbw[par][0][3];
-        if constexpr (u == 11) ovf = ovf | pbw[par][1][0] | pbw[par][1][1];
-        if constexpr (u == 15) ovf = ovf | pbw[par][1][2] | pbw[par][1][3];
-        if constexpr (u + 1 < 16) sm_x[par][(u + 1) & 1] = fast_exp2(sm_a[par][(u + 1) & 1]);
-        if constexpr (u + 2 < 16) sm_a[par][u & 1] = fmaf(sacc[par][u + 2], c2, -msc);
-        // (only values that exist take part in a pin: a pinned constant would cost a move)
-        if constexpr ((u & 3) == 3) {
-            asm volatile("" : "+v"(pbw[par][u >> 3][(u >> 1) & 3]), "+v"(ovf), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]),
-                              "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
-        } else if constexpr ((u & 1) != 0) {
-            asm volatile("" : "+v"(pbw[par][u >> 3][(u >> 1) & 3]), "+v"(sm_x[par][0]), "+v"(sm_x[par][1]),
-                              "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
-        } else {
-            asm volatile("" : "+v"(sm_x[par][0]), "+v"(sm_x[par][1]), "+v"(sm_a[par][0]), "+v"(sm_a[par][1]), "+v"(next));
-        }
-    };
-    // The uncommon case, and the first tile of every row: take the tile's row maximum (one exchange with the other
-    // half of the key rows, lane ^ 32), move the reference of the rows that exceed it, redo the tile's probabilities
-    // and rescale what was accumulated under the old reference.  `started` says whether the next sub-step (the other
-    // parity) has already taken its first values under the old reference; they are redone as well.
-    auto sm_slow = [&](auto par_c, auto started_c) __attribute__((always_inline)) {
-        constexpr int par = decltype(par_c)::value;
-        constexpr bool started = decltype(started_c)::value != 0;
-        const f32x16 &s = sacc[par];
-        float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
-#pragma unroll
-        for (int v = 3; v < 16; ++v) mx = fmaxf(mx, s[v]);
-        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-        const float tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-        const float m_new = fmaxf(m_run, tmax);
-        const bool none = m_new == -INFINITY;                 // the row has still seen nothing but masked keys
-        const float m_safe = none ? 0.0f : m_new;
-        const float alpha = fast_exp2((m_run - m_safe) * c2); // 1 for rows whose reference stays, 0 for a first reference
-        m_run = m_new;
-        msc = none ? -INFINITY : fmaf(m_safe, c2, kOff);
-        const float msc_safe = none ? 0.0f : msc;
-#pragma unroll
-        for (int v = 0; v < 16; v += 2) {
-            f32x2 pe = {fast_exp2(fmaf(s[v], c2, -msc_safe)), fast_exp2(fmaf(s[v + 1], c2, -msc_safe))};
-            pbw[par][v >> 3][(v >> 1) & 3] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pe, bf16x2));
-        }
-        if (__any(alpha != 1.0f)) {
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
-            lacc[0] *= __shfl(alpha, lane & 15, 64);
-            lacc[1] *= __shfl(alpha, (lane & 15) + 16, 64);
-        }
-        if constexpr (started) {
-            sm_a[par ^ 1][0] = fmaf(sacc[par ^ 1][0], c2, -msc);
-            sm_a[par ^ 1][1] = fmaf(sacc[par ^ 1][1], c2, -msc);
-            sm_x[par ^ 1][0] = fast_exp2(sm_a[par ^ 1][0]);
-        }
-    };
-    // Closes sub-step `par`: nothing to do unless some probability reached 2.0 (or is not a number: a row without a
-    // reference yet).
-    auto sm_finish = [&](auto par_c, auto started_c) __attribute__((always_inline)) {
-        if (__any((ovf & 0x40004000u) != 0u)) sm_slow(par_c, started_c);
-    };
-    const std::integral_constant<int, 0> c0;
-    const std::integral_constant<int, 1> c1;
-
-    // ---- one iteration of the pipeline --------------------------------------------------------------------
-    // Iteration n (block n = j_n in the K/V buffers n & 1) is one chain of 32 MFMA units
-    //   [S^T of block n+1, tile 0] [PV of block n, tile 0] [S^T of block n+1, tile 1] [PV of block n, tile 1]
-    // with the softmax chunks of sub-steps 2n+1 (EX, units 0-15), 2n+2 (MX units 9-14, EX units 16-31) and 2n+3
-    // (MX units 25-30) between them: about four VALU instructions per MFMA everywhere.  The block loads of an
-    // iteration (K of block n+2 into the buffer of K block n, V of block n+1 into the buffer of V block n-1:
-    // both buffers were last read in the iteration before) are spread over the chain and awaited at the barrier
-    // that closes the iteration.  Without a block n+1 (has_qk = 0) the chain is the 16 PV units only.
-    auto iteration = [&](auto has_qk_c, auto diag_c, auto kload_c, auto vload_c, auto clamp_c, bool diag, int key_max, int jk, int bk,
-                         int jv, int bv)
-                         __attribute__((always_inline)) {
-        constexpr bool has_qk = decltype(has_qk_c)::value != 0, may_diag = decltype(diag_c)::value != 0,
-                       kload = decltype(kload_c)::value != 0, vload = decltype(vload_c)::value != 0,
-                       clamp = decltype(clamp_c)::value != 0;
-        constexpr int n_all = has_qk ? 32 : 16;
-        auto fetch = [&](auto w_c) __attribute__((always_inline)) -> bf16x8 {
-            constexpr int w = decltype(w_c)::value;
-            constexpr int ph = has_qk ? (w >> 3) : 2 * (w >> 3) + 1, t = ph >> 1;
-            if constexpr ((ph & 1) == 0) return k_fetch(t, w & 7);
-            else return v_fetch(t, (w & 7) >> 2, w & 3);
-        };
-        static_for<kAhead>([&](auto w_c) __attribute__((always_inline)) { opnd[decltype(w_c)::value % kAhead] = fetch(w_c); });
-        static_for<n_all>([&](auto w_c) __attribute__((always_inline)) {
-            constexpr int w = decltype(w_c)::value;
-            constexpr int ph = has_qk ? (w >> 3) : 2 * (w >> 3) + 1, t = ph >> 1;
-            __builtin_amdgcn_sched_barrier(0);
-            const bf16x8 x = opnd[w % kAhead];
-            if constexpr ((ph & 1) == 0) {
-                constexpr int ks = w & 7;
-                f32x16 zero;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
-                sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qreg[ks], ks == 0 ? zero : sacc[t], 0, 0, 0);
-            } else {
-                constexpr int g = (w & 7) >> 2, db = w & 3;
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, __builtin_bit_cast(bf16x8, pbw[t][g]), oacc[db], 0, 0, 0);
-                if constexpr (db == 3)
-                    lacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones_a, __builtin_bit_cast(bf16x8, pbw[t][g]), lacc, 0, 0, 0);
-            }
-            if constexpr (w + kAhead < n_all) opnd[(w + kAhead) % kAhead] = fetch(std::integral_constant<int, (w + kAhead < n_all ? w + kAhead : 0)>{});
-            // block loads, evenly spread
-            constexpr int n_dma = (kload ? kDma : 0) + (vload ? kDma : 0);
-            if constexpr (n_dma > 0) {
-                constexpr int gap = kDmaGap * 2 * kDma <= n_all ? kDmaGap : n_all / (2 * kDma);
-                if constexpr (w % gap == gap / 2 && w / gap < 2 * kDma) {
-                    constexpr int d = w / gap;
-                    if constexpr ((d < kDma && kload) || (d >= kDma && vload)) {
-                        if constexpr (clamp) dma_clamped(d, jk, bk, jv, bv);
-                        else dma_one(d, jk, bk, jv, bv);
-                    }
-                }
-            }
-            bf16x8 &next = opnd[(w + 1) % kAhead];
-            if constexpr (has_qk) {
-                if constexpr (w < 16) ex_chunk(c1, std::integral_constant<int, w % 16>{}, next);
-                else ex_chunk(c0, std::integral_constant<int, w % 16>{}, next);
-                if constexpr (may_diag && (w == 7 || w == 23)) {
-                    if (diag) sm_mask(std::integral_constant<int, (w == 23)>{}, key_max);
-                }
-                if constexpr (w >= 9 && w < 9 + NMX) mx_chunk(c0, std::integral_constant<int, (w >= 9 && w < 9 + NMX ? w - 9 : 0)>{}, next);
-                if constexpr (w >= 25 && w < 25 + NMX) mx_chunk(c1, std::integral_constant<int, (w >= 25 && w < 25 + NMX ? w - 25 : 0)>{}, next);
-                if constexpr (w == 15) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    sm_finish(c1, c1);
-                }
-                if constexpr (w == 31) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    sm_finish(c0, c1);
-                }
-            } else {
-                if constexpr (w < 8) {
-                    ex_chunk(c1, std::integral_constant<int, (2 * w) % 16>{}, next);
-                    ex_chunk(c1, std::integral_constant<int, (2 * w + 1) % 16>{}, next);
-                }
-                if constexpr (w == 7) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    sm_finish(c1, c0);
-                }
-            }
-        });
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    auto wait_dma = []() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
-    auto close_iteration = [&]() __attribute__((always_inline)) {
-        flip_k();
-        flip_v();
-        wait_dma();
-        __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
-    };
-
-    // ---- pipeline over the visited blocks (ascending, so only the last one can be the diagonal block) ------
-    const int j_first = next_block();
-    if (j_first >= 0) {
-        int j1 = next_block();                    // block n+1 at the top of iteration n
-        int j2 = j1 >= 0 ? next_block() : -1;     // block n+2
-#pragma unroll
-        for (int d = 0; d < 2 * kDma; ++d) dma_clamped(d, j_first, 0, j_first, 0);
-        if (j1 >= 0) {
-#pragma unroll
-            for (int d = 0; d < kDma; ++d) dma_clamped(d, j1, 1, -1, 0);
-        }
-        wait_dma();
-        __syncthreads();
-        // prologue: S^T of block 0, the whole softmax of its tile 0 and the maximum of its tile 1, unhidden
-        static_for<16>([&](auto w_c) __attribute__((always_inline)) {
-            constexpr int w = decltype(w_c)::value, t = w >> 3, ks = w & 7;
-            f32x16 zero;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
-            sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_fetch(t, ks), qreg[ks], ks == 0 ? zero : sacc[t], 0, 0, 0);
-        });
-        if (j1 < 0 && needs_mask(j_first)) {
-            const int km = key_max_of(j_first);
-            sm_mask(c0, km);
-            sm_mask(c1, km);
-        }
-        sm_slow(c0, c0);
-        static_for<NMX>([&](auto m_c) __attribute__((always_inline)) { mx_chunk(c1, m_c, opnd[0]); });
-        flip_k();                                 // block 1's K is in buffer 1
-        __syncthreads();                          // K buffer 0 is reloaded from the first iteration on
-        int n = 0;
-        if (j1 >= 0) {
-#pragma unroll 1
-            while (j2 >= 0 && j2 != j_short) {    // block n+2 exists and is a whole block: plain loads, no masking
-                iteration(c1, c0, c1, c1, c0, false, 0, j2, n & 1, j1, (n + 1) & 1);
-                close_iteration();
-                j1 = j2;
-                j2 = next_block();
-                ++n;
-            }
-            if (j2 >= 0) {                        // block n+2 is the shorter last block of the sequence
-                iteration(c1, c0, c1, c1, c1, false, 0, j2, n & 1, j1, (n + 1) & 1);
-                close_iteration();
-                j1 = j2;
-                j2 = -1;
-                ++n;
-            }
-            // block n+1 is the last one: no K block to load; it may be the diagonal and / or the shorter block
-            iteration(c1, c1, c0, c1, c1, needs_mask(j1), key_max_of(j1), -1, 0, j1, (n + 1) & 1);
-            close_iteration();
-        }
-        // the last block's P V
-        iteration(c0, c0, c0, c0, c0, false, 0, -1, 0, -1, 0);
-    }
-    __syncthreads();
-
-    // ---- merge the two key halves through LDS, normalise, store -------------------------------------
-    // row sums: lanes 0-15 hold those of queries 0-15 in lacc[0] and of queries 16-31 in lacc[1]
-    const float l_lo = __shfl(lacc[0], lane & 15, 64), l_hi = __shfl(lacc[1], lane & 15, 64);   // (all lanes active)
-    const float l_run = lr < 16 ? l_lo : l_hi;
-    float *mo = reinterpret_cast<float *>(lds) + qq * (66 * 64);      // [64 + 2 slots][64 lanes] per query slice
-    float *ml = mo + 64 * 64;
-    if (kh == 1) {
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mo[(db * 16 + v) * 64 + lane] = oacc[db][v];
-        ml[lane] = m_run;
-        ml[64 + lane] = l_run;
-    }
-    __syncthreads();
-    if (kh == 0) {
-        const float m1 = C::KW == 2 ? ml[lane] : -INFINITY, l1 = C::KW == 2 ? ml[64 + lane] : 0.0f;
-        const float m0 = m_run, l0 = l_run;
-        const float m_t = fmaxf(m0, m1);
-        const bool empty = m_t == -INFINITY;
-        const float m_s = empty ? 0.0f : m_t;
-        const float a0 = fast_exp2((m0 - m_s) * c2), a1 = fast_exp2((m1 - m_s) * c2);
-        const float l_t = l0 * a0 + l1 * a1;
-        const float inv = empty ? 0.0f : 1.0f / l_t;
-        const bool row_exists = 32 * qq + lr < q_rows;
-        const int64_t tok = tok0 + (int64_t)i * S + 32 * qq + lr;
-        bf16_t *dst = a.o + tok * a.o_stride_tok + (int64_t)head * a.o_stride_head;
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                float r[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    int v = 4 * g + e;
-                    float o1 = C::KW == 2 ? mo[(db * 16 + v) * 64 + lane] : 0.0f;
-                    r[e] = (oacc[db][v] * a0 + o1 * a1) * inv;
-                }
-                u32x2 w;
-                w[0] = f32_to_bf16_rne(r[0]) | (f32_to_bf16_rne(r[1]) << 16);
-                w[1] = f32_to_bf16_rne(r[2]) | (f32_to_bf16_rne(r[3]) << 16);
-                if (row_exists) *reinterpret_cast<u32x2 *>(dst + 32 * db + 8 * g + 4 * lh) = w;
-            }
-        }
-        if (a.lse != nullptr && lh == 0 && row_exists)
-            a.lse[(int64_t)head * a.total_tokens + tok] = empty ? -INFINITY : (__log2f(l_t) + m_t * c2 + kOff) * kLn2;
-    }
-}
-
-template <int S, bool CAUSAL, bool DENSE>
-static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
-{
-    using C = AttnCfg<S>;
-    static LdsAttr attr;
-    hipError_t e = attr.set(reinterpret_cast<const void *>(&attention_kernel<S, CAUSAL, DENSE>), C::kLdsBytes);
-    if (e != hipSuccess) return e;
-    if (a.n_heads_q == 0 || a.NQ == 0) return hipSuccess;
-    const int G = a.n_heads_q / a.n_heads_kv;
-    AttnOrder ord;
-    ord.HG = G % 2 == 0 ? 2 : 1;
-    ord.R = 32 / ord.HG;
-    ord.n_rg = (a.NQ + ord.R - 1) / ord.R;
-    ord.n_chunks = ord.n_rg * (a.n_heads_q / ord.HG);
-    ord.head_major = 0;
-    const int64_t per_xcd = (ord.n_chunks + kNumXcd - 1) / kNumXcd;
-    const int64_t nblk = per_xcd * kNumXcd * ord.R * ord.HG;
-    hipLaunchKernelGGL((attention_kernel<S, CAUSAL, DENSE>), dim3((unsigned)nblk), dim3(C::NT), C::kLdsBytes, stream,
-                       a, ord);
-    return hipGetLastError();
-}
+hipError_t attn_dispatch_d128(const AttnArgs &a, hipStream_t stream) { return attn_dispatch_t<128>(a, stream); }
 
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream)
 {
-    if (a.head_dim != kHeadDim) return launch_attention_generic(a, stream);
-    const bool dense = a.mask == nullptr;
-#define US_AT(SS, CA, DE) \
-    if (a.S == SS && (a.causal != 0) == CA && dense == DE) return attn_launch_t<SS, CA, DE>(a, stream)
-    US_AT(128, true, true); US_AT(128, true, false); US_AT(128, false, true); US_AT(128, false, false);
-    US_AT(64, true, true); US_AT(64, true, false); US_AT(64, false, true); US_AT(64, false, false);
-#undef US_AT
+    switch (a.head_dim) {
+        case 64: return attn_dispatch_d64(a, stream);
+        case 128: return attn_dispatch_d128(a, stream);
+        case 256: return attn_dispatch_d256(a, stream);
+    }
     return hipErrorInvalidValue;
 }
 

@@ -21,7 +21,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kHeadDim = 128;           // the head dimension the pipelined attention kernel is written for
 constexpr int kMaxSeqs = UNISPARSE_MAX_SEQS;
 constexpr int kNumXcd = 8;              // MI355X: 8 accelerator dies, workgroups are dealt round-robin to them
 constexpr float kLog2e = 1.4426950408889634f;
@@ -163,8 +162,8 @@ struct AttnArgs {
     int64_t total_tokens;
     float scale_log2;
 };
-// head_dim 128: the software-pipelined kernel of attention.hip; 64 and 256: the plain kernel of attention_generic.hip
+// one software-pipelined kernel (attention_kernel.h), instantiated per head dimension, block size, causality and
+// dense / block-sparse
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream);
-hipError_t launch_attention_generic(const AttnArgs &a, hipStream_t stream);
 
 }  // namespace us

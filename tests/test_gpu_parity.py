@@ -81,12 +81,24 @@ def test_dense_attention_any_length(ctx, oracle):
 @pytest.mark.parametrize("kind", ["rising", "falling", "spikes", "ramp"])
 @pytest.mark.parametrize("S,causal", [(128, True), (128, False), (64, True)])
 def test_attention_with_logits_spanning_hundreds_of_units(ctx, oracle, kind, S, causal):
+    steep_logits_check(ctx, oracle, kind, S, causal, 128)
+
+
+@pytest.mark.parametrize("d", [64, 256])
+@pytest.mark.parametrize("kind,S,causal", [("rising", 128, True), ("spikes", 128, False), ("ramp", 64, True),
+                                           ("falling", 128, True)])
+def test_attention_with_steep_logits_other_head_dims(ctx, oracle, d, kind, S, causal):
+    """The same at head dimensions 64 and 256 (at 256 a block is walked in two stages of 64 keys)."""
+    steep_logits_check(ctx, oracle, kind, S, causal, d)
+
+
+def steep_logits_check(ctx, oracle, kind, S, causal, d):
     """Rows whose logits differ by up to ~190 natural-log units: the attention kernels keep one reference value per
     row for their exponentials and move it only when a probability would grow past a bound, so these inputs drive
     that path (a new reference in every block, in the middle of tiles, in nearly every tile) and its opposite (terms
     that vanish against an early reference).  Dense and block-sparse (random half of the blocks) against the oracle,
     ragged last block included."""
-    w = W.steep_logits(kind, H=2, Hkv=1, lengths=(8 * S + 40, 3 * S), S=S, causal=causal, seed=70 + S)
+    w = W.steep_logits(kind, H=2, Hkv=1, lengths=(8 * S + 40, 3 * S), S=S, causal=causal, seed=70 + S, d=d)
     q, k, v = PU.device_tensors(w)
     qf, kf, vf = w.f32()
     p = PU.problem_of(w)
