@@ -17,8 +17,7 @@
  *   every buffer (inputs, outputs, workspace).  The library allocates no device memory,
  *   never synchronises the device or a stream, and enqueues work only on the stream given.
  * - Element type of Q, K, V, O and of the composite tokens is bf16 (2 bytes).  head_dim d = 64, 128 or 256
- *   (128 is the dimension of every model the paper measures and the one the fast attention kernel is written
- *   for; 64 and 256 run a plainer kernel).
+ *   (128 is the dimension of every model the paper measures).
  * - A problem is a packed batch of B sequences ("varlen"): tokens of all sequences are
  *   concatenated along the token axis, sequence b owning tokens [cu_seqlens[b], cu_seqlens[b+1]).
  *   Sequences never interact.  A length that is not a multiple of block_size gives a shorter last block
