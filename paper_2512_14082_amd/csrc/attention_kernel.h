@@ -295,15 +295,16 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
         }
     }
     // PV operand: tile t, group g (16 keys) of the tile, dims block db
-    auto v_fetch = [&](int t, int g, int db) __attribute__((always_inline)) -> bf16x8 {
-        lds_ptr p0 = vaddr[db] + (32 * t + 16 * g) * RB;
+    // (`off`: compile-time byte offset of the buffer, for the unrolled main loop whose base addresses never move)
+    auto v_fetch = [&](int t, int g, int db, int off) __attribute__((always_inline)) -> bf16x8 {
+        lds_ptr p0 = vaddr[db] + ((32 * t + 16 * g) * RB + off);
         short4v x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)p0);
         short4v x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(p0 + 8 * RB));
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7));
     };
     // QK operand: tile t, k-step ks
-    auto k_fetch = [&](int t, int ks) __attribute__((always_inline)) -> bf16x8 {
-        return *(lds_b8_ptr)(kaddr[ks] + 32 * t * RB);
+    auto k_fetch = [&](int t, int ks, int off) __attribute__((always_inline)) -> bf16x8 {
+        return *(lds_b8_ptr)(kaddr[ks] + (32 * t * RB + off));
     };
     // kaddr / vaddr point into buffer 0 or 1; the other buffer is one block further or back
     int k_flip = C::kTileBytes, v_flip = C::kTileBytes;
@@ -447,9 +448,14 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
     // iteration (K of block n+2 into the buffer of K block n, V of block n+1 into the buffer of V block n-1:
     // both buffers were last read in the iteration before) are spread over the chain and awaited at the barrier
     // that closes the iteration.  Without a stage n+1 (has_qk = 0) the chain is the PV units only.
-    auto iteration = [&](auto has_qk_c, auto diag_c, auto kload_c, auto vload_c, auto clamp_c, bool diag, int key_max, int jk, int bk,
-                         int jv, int bv)
+    // buf_c: 0 = the address registers point at the buffers this iteration reads (they are flipped between
+    // iterations); 1 / 2 = they point at buffer 0 and this is an even / odd iteration of the unrolled main loop: K of
+    // stage n+1 sits in buffer (n+1) & 1, V of stage n in buffer n & 1, reached through immediate offsets.
+    auto iteration = [&](auto has_qk_c, auto diag_c, auto kload_c, auto vload_c, auto clamp_c, auto buf_c, bool diag, int key_max,
+                         int jk, int bk, int jv, int bv)
                          __attribute__((always_inline)) {
+        constexpr int buf = decltype(buf_c)::value;
+        constexpr int k_off = buf == 1 ? C::kTileBytes : 0, v_off = buf == 2 ? C::kTileBytes : 0;
         constexpr bool has_qk = decltype(has_qk_c)::value != 0, may_diag = decltype(diag_c)::value != 0,
                        kload = decltype(kload_c)::value != 0, vload = decltype(vload_c)::value != 0,
                        clamp = decltype(clamp_c)::value != 0;
@@ -461,8 +467,8 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
             constexpr int ph = has_qk ? (w / UPP) : 2 * (w / UPP) + 1, t = ph >> 1, u = w % UPP;
 #pragma unroll
             for (int m = 0; m < MPU; ++m) {
-                if constexpr ((ph & 1) == 0) dst[m] = k_fetch(t, u * MPU + m);
-                else dst[m] = v_fetch(t, u / UPG, (u % UPG) * MPU + m);
+                if constexpr ((ph & 1) == 0) dst[m] = k_fetch(t, u * MPU + m, k_off);
+                else dst[m] = v_fetch(t, u / UPG, (u % UPG) * MPU + m, v_off);
             }
         };
         static_for<(kAhead < n_all ? kAhead : n_all)>([&](auto w_c) __attribute__((always_inline)) { fetch(w_c, opnd[decltype(w_c)::value % kAhead]); });
@@ -537,6 +543,11 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
         __builtin_amdgcn_sched_barrier(0);
     };
     auto wait_dma = []() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+    auto close_unrolled = [&]() __attribute__((always_inline)) {
+        wait_dma();
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+    };
     auto close_iteration = [&]() __attribute__((always_inline)) {
         flip_k();
         flip_v();
@@ -565,7 +576,7 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
             f32x16 zero;
 #pragma unroll
             for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
-            sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_fetch(t, ks), qreg[ks], ks == 0 ? zero : sacc[t], 0, 0, 0);
+            sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_fetch(t, ks, 0), qreg[ks], ks == 0 ? zero : sacc[t], 0, 0, 0);
         });
         if (needs_mask(j_first)) {
             const int km = key_max_of(j_first);
@@ -574,32 +585,47 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
         }
         sm_slow(c0, c0);
         static_for<NMX>([&](auto m_c) __attribute__((always_inline)) { mx_chunk(c1, m_c, opnd[0][0]); });
-        flip_k();                                 // block 1's K is in buffer 1
         __syncthreads();                          // K buffer 0 is reloaded from the first iteration on
         int n = 0;
         if (j1 >= 0) {
+            // Main loop, two iterations per trip so that the buffer an iteration reads is known at compile time and
+            // the address registers never move: while stage n+2 exists and is whole and stage n+1 needs no mask.
+            auto plain = [&]() __attribute__((always_inline)) -> bool { return j2 >= 0 && j2 != j_short && !needs_mask(j1); };
+            const std::integral_constant<int, 2> c2_;
 #pragma unroll 1
-            while (j2 >= 0 && j2 != j_short && !needs_mask(j1)) {   // stage n+2 exists and is whole, stage n+1 needs no mask
-                iteration(c1, c0, c1, c1, c0, false, 0, j2, n & 1, j1, (n + 1) & 1);
-                close_iteration();
+            while (plain()) {
+                iteration(c1, c0, c1, c1, c0, c1, false, 0, j2, 0, j1, 1);          // n even
+                close_unrolled();
+                j1 = j2;
+                j2 = next_block();
+                ++n;
+                if (!plain()) break;
+                iteration(c1, c0, c1, c1, c0, c2_, false, 0, j2, 1, j1, 0);         // n odd
+                close_unrolled();
                 j1 = j2;
                 j2 = next_block();
                 ++n;
             }
+            // from here on the address registers follow the buffers: K of stage n+1, V of stage n
+            if ((n & 1) == 0) {
+                flip_k();
+            } else {
+                flip_v();
+            }
 #pragma unroll 1
             while (j2 >= 0) {                     // the last stages of the row: clamped loads, masked tiles
-                iteration(c1, c1, c1, c1, c1, needs_mask(j1), key_max_of(j1), j2, n & 1, j1, (n + 1) & 1);
+                iteration(c1, c1, c1, c1, c1, c0, needs_mask(j1), key_max_of(j1), j2, n & 1, j1, (n + 1) & 1);
                 close_iteration();
                 j1 = j2;
                 j2 = next_block();
                 ++n;
             }
             // stage n+1 is the last one: no K stage to load; it may lie on the diagonal and / or be the shorter one
-            iteration(c1, c1, c0, c1, c1, needs_mask(j1), key_max_of(j1), -1, 0, j1, (n + 1) & 1);
+            iteration(c1, c1, c0, c1, c1, c0, needs_mask(j1), key_max_of(j1), -1, 0, j1, (n + 1) & 1);
             close_iteration();
         }
         // the last block's P V
-        iteration(c0, c0, c0, c0, c0, false, 0, -1, 0, -1, 0);
+        iteration(c0, c0, c0, c0, c0, c0, false, 0, -1, 0, -1, 0);
     }
     __syncthreads();
 
