@@ -7,7 +7,7 @@
 // 128.  Each wavefront keeps its 64 query rows as MFMA B operands in registers and computes
 // 32-key x 64-query logit tiles transposed (S^T = K~ Q~^T, v_mfma_f32_32x32x16_bf16), so that every
 // lane owns whole query rows and the softmax statistics are lane-local.  Two sweeps over the
-// keys: the first finds each row's maximum and denominator, the second sums the normalised
+// keys: the first finds a reference value and the denominator of each row, the second sums the normalised
 // probabilities over the composite keys of each key block (in registers), then over the
 // composite queries of each query block (cross-lane), and stores Score(i, j).
 #pragma once
@@ -153,7 +153,7 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
     for (int qb = 0; qb < QT; ++qb) {
         m_run[qb] = -INFINITY;
         l_run[qb] = 0.0f;
-        mc[qb] = 0.0f;
+        mc[qb] = -INFINITY;             // first sweep: the scaled reference value (none yet); second sweep: the final one
         wnorm[qb] = 0.0f;
     }
 
@@ -172,23 +172,45 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
                 dst[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][ks], ks == 0 ? zero : dst[qb], 0, 0, 0);
         }
     };
-    // first sweep: running maximum and denominator of every composite query row
+    // first sweep: a reference value and the denominator (relative to it) of every composite query row.  Softmax is
+    // shift-invariant, so the reference need not be the row maximum: it is the maximum of the first tile that shows
+    // the row a visible key and moves only when a tile's sum of exponentials passes 2^40 (or is not finite: no
+    // reference yet, or a logit hundreds of units above it).  The common case is one fma, one exponential and one
+    // add per value; the tile is redone with its true maximum otherwise.
     auto stats_tile = [&](const f32x16 (&src)[QT]) __attribute__((always_inline)) {
+        constexpr float kBig = 1099511627776.0f;           // 2^40
+        float sum[QT];
+        bool need[QT], redo = false;
 #pragma unroll
         for (int qb = 0; qb < QT; ++qb) {
-            float mx = src[qb][0];
+            sum[qb] = 0.0f;
 #pragma unroll
-            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, src[qb][v]);
-            float m_new = fmaxf(m_run[qb], mx);
-            float m_safe = m_new == -INFINITY ? 0.0f : m_new;
-            float alpha = fast_exp2((m_run[qb] - m_safe) * c2);
-            float msc = m_safe * c2;
-            float sum = 0.0f;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sum += fast_exp2(fmaf(src[qb][v], c2, -msc));
-            l_run[qb] = l_run[qb] * alpha + sum;
-            m_run[qb] = m_new;
+            for (int v = 0; v < 16; ++v) sum[qb] += fast_exp2(fmaf(src[qb][v], c2, -mc[qb]));
+            need[qb] = !(sum[qb] <= kBig);
+            redo = redo || need[qb];
         }
+        if (__any(redo)) {                                 // (a row's reference moves only on that row's own account)
+#pragma unroll
+            for (int qb = 0; qb < QT; ++qb) {
+                float mx = src[qb][0];
+#pragma unroll
+                for (int v = 1; v < 16; ++v) mx = fmaxf(mx, src[qb][v]);
+                const float m_new = need[qb] ? fmaxf(m_run[qb], mx) : m_run[qb];
+                const bool none = m_new == -INFINITY;      // nothing visible to this row yet
+                const float m_safe = none ? 0.0f : m_new;
+                const float alpha = fast_exp2((m_run[qb] - m_safe) * c2);
+                const float msc = m_safe * c2;
+                float sm = 0.0f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sm += fast_exp2(fmaf(src[qb][v], c2, -msc));
+                sum[qb] = sm;
+                l_run[qb] *= alpha;
+                m_run[qb] = m_new;
+                mc[qb] = none ? -INFINITY : msc;
+            }
+        }
+#pragma unroll
+        for (int qb = 0; qb < QT; ++qb) l_run[qb] += sum[qb];
     };
     // second sweep: normalised probabilities summed over the composite keys of each key block (registers),
     // then over the composite queries of each query block (lanes), stored as Score(i, j)
