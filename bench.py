@@ -4,7 +4,7 @@ speedup over this library's own dense attention kernel.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg1|cfg4|cfg5]
 
-A step = one pass of the whole hot path (pool -> compressed scores -> selection -> sparse attention)
+A step = one pass of the whole hot path (pool -> compressed scores -> selection -> row ranking -> sparse attention)
 over one synthetic layer already resident in HBM.  Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -149,7 +149,7 @@ def main():
 
     def step():
         ctx.build_mask(p, s, q, k, lay, workspace=ws, mask=mask)
-        ctx.sparse_attn(p, q, k, v, mask, lay, out=o)
+        ctx.sparse_attn(p, q, k, v, mask, lay, out=o, workspace=ws)      # unisparse_sparse_attn_ws: ranked work order
 
     if args.profile_copy_mb > 0:
         src = torch.empty(args.profile_copy_mb << 20, dtype=torch.uint8, device="cuda")
@@ -176,7 +176,7 @@ def main():
     # scores for the selection-only timing
     _, sc = ctx.build_mask(p, s, q, k, lay, workspace=ws, mask=mask, want_score=True)
     ms_select = _time_ms(lambda: ctx.select_blocks(p, s, sc, mask=mask), reps)
-    ms_sparse = _time_ms(lambda: ctx.sparse_attn(p, q, k, v, mask, lay, out=o), reps)
+    ms_sparse = _time_ms(lambda: ctx.sparse_attn(p, q, k, v, mask, lay, out=o, workspace=ws), reps)
     ms_dense = _time_ms(lambda: ctx.full_attn(p, q, k, v, lay, out=od), args.dense_reps, warm=1)
     torch.cuda.synchronize()
 

@@ -25,7 +25,8 @@ EXPORTS = [
     "unisparse_create", "unisparse_destroy", "unisparse_status_string", "unisparse_mask_row_words",
     "unisparse_mask_words", "unisparse_score_elems", "unisparse_workspace_bytes", "unisparse_avgpool_seq",
     "unisparse_pool_seq_varlen",
-    "unisparse_build_mask", "unisparse_build_mask_static", "unisparse_select_blocks", "unisparse_sparse_attn", "unisparse_full_attn",
+    "unisparse_build_mask", "unisparse_build_mask_static", "unisparse_select_blocks", "unisparse_sparse_attn",
+    "unisparse_sparse_attn_ws", "unisparse_attn_workspace_bytes", "unisparse_full_attn",
     "unisparse_attn",
 ]
 
@@ -71,7 +72,7 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.unisparse_destroy.restype = None
     lib.unisparse_status_string.argtypes = [ctypes.c_int]
     lib.unisparse_status_string.restype = ctypes.c_char_p
-    for name in ("unisparse_mask_row_words", "unisparse_mask_words"):
+    for name in ("unisparse_mask_row_words", "unisparse_mask_words", "unisparse_attn_workspace_bytes"):
         getattr(lib, name).argtypes = [PP]
         getattr(lib, name).restype = sz
     for name in ("unisparse_score_elems", "unisparse_workspace_bytes"):
@@ -89,6 +90,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.unisparse_select_blocks.restype = ctypes.c_int
     lib.unisparse_sparse_attn.argtypes = [vp, PP, _Tensor, _Tensor, _Tensor, vp, _Tensor, vp, vp]
     lib.unisparse_sparse_attn.restype = ctypes.c_int
+    lib.unisparse_sparse_attn_ws.argtypes = [vp, PP, _Tensor, _Tensor, _Tensor, vp, _Tensor, vp, vp, sz, vp]
+    lib.unisparse_sparse_attn_ws.restype = ctypes.c_int
     lib.unisparse_full_attn.argtypes = [vp, PP, _Tensor, _Tensor, _Tensor, _Tensor, vp, vp]
     lib.unisparse_full_attn.restype = ctypes.c_int
     lib.unisparse_attn.argtypes = [vp, PP, SP, _Tensor, _Tensor, _Tensor, vp, sz, vp, _Tensor, vp, vp]
@@ -291,13 +294,24 @@ class Context:
         _check(self.lib.unisparse_select_blocks(self.handle, p.c, s.c, score.data_ptr(), m.data_ptr(), _stream()))
         return m
 
+    def attn_workspace_bytes(self, p: Problem) -> int:
+        return int(self.lib.unisparse_attn_workspace_bytes(p.c))
+
     def sparse_attn(self, p: Problem, q, k, v, mask: torch.Tensor, layout: str = "htd",
-                    out: Optional[torch.Tensor] = None, want_lse: bool = False):
+                    out: Optional[torch.Tensor] = None, want_lse: bool = False,
+                    workspace: Optional[torch.Tensor] = None):
+        """``unisparse_sparse_attn``, or ``unisparse_sparse_attn_ws`` when a workspace tensor (uint8, device) is given."""
         o = out if out is not None else torch.empty_like(q)
         lse = torch.empty((p.n_heads_q, p.total_tokens), dtype=torch.float32, device=q.device) if want_lse else None
-        _check(self.lib.unisparse_sparse_attn(self.handle, p.c, _view(q, layout), _view(k, layout), _view(v, layout),
-                                              mask.data_ptr(), _view(o, layout),
-                                              lse.data_ptr() if want_lse else None, _stream()))
+        if workspace is None:
+            _check(self.lib.unisparse_sparse_attn(self.handle, p.c, _view(q, layout), _view(k, layout), _view(v, layout),
+                                                  mask.data_ptr(), _view(o, layout),
+                                                  lse.data_ptr() if want_lse else None, _stream()))
+        else:
+            _check(self.lib.unisparse_sparse_attn_ws(self.handle, p.c, _view(q, layout), _view(k, layout),
+                                                     _view(v, layout), mask.data_ptr(), _view(o, layout),
+                                                     lse.data_ptr() if want_lse else None, workspace.data_ptr(),
+                                                     workspace.numel(), _stream()))
         return o, lse
 
     def full_attn(self, p: Problem, q, k, v, layout: str = "htd", out: Optional[torch.Tensor] = None,

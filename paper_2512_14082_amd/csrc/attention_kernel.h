@@ -74,13 +74,22 @@ template <int D> __device__ __forceinline__ int v_swizzle(int row) { return D ==
 // head) x (R consecutive query-block rows), 32 workgroups that read the same K/V; chunk number ci runs on
 // XCD ci % 8, longest rows first, and the head group is rotated against the row group so that every XCD
 // sees every head (masks of different heads have different densities).
+//
+// Ranked variant (block-sparse only, when the caller gives scratch memory): the rows of a chunk are not R consecutive
+// rows but R rows of consecutive RANK, every head's rows ranked by (sequence, number of selected blocks descending).
+// Workgroups of a chunk then have about the same length, start together and stay together on their way through the
+// K/V blocks they share, which is what the L2 needs: on the 128K configuration the traffic behind the L2 halves.  The
+// rank table is made by attn_rank_kernel from the mask alone, so the order - and with it nothing but the order: every
+// row's arithmetic is the same - is a function of the mask.
 struct AttnOrder {
     int R;           // rows per chunk
     int HG;          // query heads (of one key head) per chunk
     int n_rg;        // row groups = ceil(NQ / R)
     int n_chunks;    // n_rg * (n_heads_q / HG)
     int head_major;  // 1: all row groups of key head 0, then head 1, ... ; 0: row groups outermost, heads rotated
+    const int32_t *table;   // ranked variant: (head << 20 | row) per workgroup id, -1 = no work; NULL = formula below
 };
+constexpr int kRankMaxRows = 8192;      // rows per head the rank kernel sorts (in LDS)
 
 template <int D, int S, bool CAUSAL, bool DENSE>
 __global__ __launch_bounds__((AttnCfg<S, D>::NT)) __attribute__((amdgpu_waves_per_eu(AttnCfg<S, D>::kWaves, AttnCfg<S, D>::kWaves)))
@@ -110,9 +119,14 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
     const int hg = ord.head_major ? ci / ord.n_rg : (ci % n_hg + rg) % n_hg;
     // consecutive workgroups of an XCD go to different shader engines: vary the row, not the head, fastest,
     // so that no engine collects all workgroups of a dense (or sparse) head
-    const int row = a.NQ - 1 - (rg * ord.R + slot % ord.R);
+    int row = a.NQ - 1 - (rg * ord.R + slot % ord.R);
+    int head = hg * ord.HG + slot / ord.R;
+    if (!DENSE && ord.table != nullptr) {                    // ranked: same chunk, same head, the row of that rank
+        const int e = __builtin_amdgcn_readfirstlane(ord.table[blockIdx.x]);
+        row = e < 0 ? -1 : (e & 0xfffff);
+        head = e < 0 ? head : (e >> 20);
+    }
     if (row < 0) return;
-    const int head = hg * ord.HG + slot / ord.R;
     const int kvh = head / G;
     int seq, i, nb;
     locate_row(a.st, S, row, seq, i, nb);
@@ -680,6 +694,9 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
     }
 }
 
+// fills a.sched with the ranked work order of `ord` (defined in attention.hip)
+hipError_t launch_attention_rank(const AttnArgs &a, const AttnOrder &ord, hipStream_t stream);
+
 template <int D, int S, bool CAUSAL, bool DENSE>
 static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
 {
@@ -695,8 +712,23 @@ static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
     ord.n_rg = (a.NQ + ord.R - 1) / ord.R;
     ord.n_chunks = ord.n_rg * (a.n_heads_q / ord.HG);
     ord.head_major = 0;
+    ord.table = nullptr;
+    // ranked order when the caller gave scratch for it; long rows (>= 960 blocks) then do best with chunks of one head
+    const bool ranked = !DENSE && a.sched != nullptr && a.NQ <= kRankMaxRows && a.n_heads_q < 2048 &&
+                        (int64_t)attention_sched_bytes(a.n_heads_q, a.n_heads_kv, a.NQ) <= a.sched_bytes;
+    if (ranked && a.W >= 16) {
+        ord.HG = 1;
+        ord.R = 32;
+        ord.n_rg = (a.NQ + ord.R - 1) / ord.R;
+        ord.n_chunks = ord.n_rg * a.n_heads_q;
+    }
     const int64_t per_xcd = (ord.n_chunks + kNumXcd - 1) / kNumXcd;
     const int64_t nblk = per_xcd * kNumXcd * ord.R * ord.HG;
+    if (ranked) {
+        e = launch_attention_rank(a, ord, stream);
+        if (e != hipSuccess) return e;
+        ord.table = a.sched;
+    }
     hipLaunchKernelGGL((attention_kernel<D, S, CAUSAL, DENSE>), dim3((unsigned)nblk), dim3(C::NT), C::kLdsBytes, stream,
                        a, ord);
     return hipGetLastError();

@@ -188,7 +188,7 @@ unisparse_status select_impl(const unisparse_problem *p, const unisparse_select 
 
 unisparse_status attn_impl(const unisparse_ctx *ctx, const unisparse_problem *p, const Geom &g, unisparse_tensor Q, unisparse_tensor K,
                            unisparse_tensor V, const uint64_t *M, unisparse_tensor O, float *lse,
-                           hipStream_t stream)
+                           hipStream_t stream, void *sched = nullptr, size_t sched_bytes = 0)
 {
     unisparse_status st;
     if ((st = check_tensor(Q, p->head_dim)) != UNISPARSE_OK) return st;
@@ -215,6 +215,8 @@ unisparse_status attn_impl(const unisparse_ctx *ctx, const unisparse_problem *p,
     a.W = g.W;
     a.total_tokens = g.T;
     a.scale_log2 = scale_log2(p);
+    a.sched = reinterpret_cast<int32_t *>(sched);
+    a.sched_bytes = (int64_t)sched_bytes;
     return launch_attention(a, stream) == hipSuccess ? UNISPARSE_OK : UNISPARSE_ERR_HIP;
 }
 
@@ -293,7 +295,9 @@ size_t unisparse_workspace_bytes(const unisparse_problem *p, const unisparse_sel
     Geom g;
     HeadGeom hg;
     if (check_problem(p, &g) != UNISPARSE_OK || check_select(p, s, &hg) != UNISPARSE_OK) return 0;
-    return carve(p, s, g, hg, true).total + 256;
+    // (also enough for unisparse_sparse_attn_ws, so that unisparse_attn can hand the same buffer on)
+    const size_t build = carve(p, s, g, hg, true).total, attn = attention_sched_bytes(p->n_heads_q, p->n_heads_kv, g.NQ);
+    return (build > attn ? build : attn) + 256;
 }
 
 unisparse_status unisparse_avgpool_seq(unisparse_ctx *ctx, unisparse_tensor x, int32_t n_heads, int64_t total_tokens,
@@ -444,6 +448,36 @@ unisparse_status unisparse_sparse_attn(unisparse_ctx *ctx, const unisparse_probl
     return attn_impl(ctx, p, g, Q, K, V, M, O, lse, (hipStream_t)stream);
 }
 
+size_t unisparse_attn_workspace_bytes(const unisparse_problem *p)
+{
+    Geom g;
+    if (check_problem(p, &g) != UNISPARSE_OK) return 0;
+    return attention_sched_bytes(p->n_heads_q, p->n_heads_kv, g.NQ) + 256;
+}
+
+unisparse_status unisparse_sparse_attn_ws(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor Q,
+                                          unisparse_tensor K, unisparse_tensor V, const uint64_t *M,
+                                          unisparse_tensor O, float *lse, void *workspace, size_t workspace_bytes,
+                                          void *stream)
+{
+    if (ctx == nullptr || M == nullptr) return UNISPARSE_ERR_NULL;
+    if (((uintptr_t)M & 7) != 0) return UNISPARSE_ERR_SHAPE;          // mask words are 8-byte loads and stores
+    Geom g;
+    unisparse_status st;
+    if ((st = check_problem(p, &g)) != UNISPARSE_OK) return st;
+    unsigned char *base = nullptr;
+    size_t avail = 0;
+    if (workspace != nullptr) {
+        base = reinterpret_cast<unsigned char *>(align256((size_t)(uintptr_t)workspace));
+        const size_t lead = (size_t)(base - reinterpret_cast<unsigned char *>(workspace));
+        const size_t need = attention_sched_bytes(p->n_heads_q, p->n_heads_kv, g.NQ);
+        if (workspace_bytes < need + lead) return UNISPARSE_ERR_WORKSPACE;
+        avail = workspace_bytes - lead;
+    }
+    if (g.T == 0) return check_tensor(Q, p->head_dim);
+    return attn_impl(ctx, p, g, Q, K, V, M, O, lse, (hipStream_t)stream, base, avail);
+}
+
 unisparse_status unisparse_full_attn(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor Q,
                                      unisparse_tensor K, unisparse_tensor V, unisparse_tensor O, float *lse,
                                      void *stream)
@@ -464,9 +498,11 @@ unisparse_status unisparse_attn(unisparse_ctx *ctx, const unisparse_problem *p, 
     if (p == nullptr) return UNISPARSE_ERR_NULL;
     if ((st = check_tensor(V, p->head_dim)) != UNISPARSE_OK) return st;
     if ((st = check_tensor(O, p->head_dim)) != UNISPARSE_OK) return st;
+    if (workspace_bytes < unisparse_attn_workspace_bytes(p)) return UNISPARSE_ERR_WORKSPACE;
     st = unisparse_build_mask(ctx, p, s, Q, K, workspace, workspace_bytes, M, nullptr, stream);
     if (st != UNISPARSE_OK) return st;
-    return unisparse_sparse_attn(ctx, p, Q, K, V, M, O, lse, stream);
+    // the mask is built: the workspace is free again and serves the attention kernel's work order
+    return unisparse_sparse_attn_ws(ctx, p, Q, K, V, M, O, lse, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -161,7 +161,11 @@ struct AttnArgs {
     int32_t head_dim;
     int64_t total_tokens;
     float scale_log2;
+    int32_t *sched;          // optional scratch for a mask-dependent work order (block-sparse only), NULL = none
+    int64_t sched_bytes;
 };
+// bytes of AttnArgs::sched that let launch_attention rank the rows of every head by their number of selected blocks
+size_t attention_sched_bytes(int n_heads_q, int n_heads_kv, int NQ);
 // one software-pipelined kernel (attention_kernel.h), instantiated per head dimension, block size, causality and
 // dense / block-sparse
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream);

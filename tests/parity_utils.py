@@ -193,9 +193,12 @@ def sampled_config_check(ctx, oracle, w: W.Workload, seed, n_random=16, attn_hea
     ws, m_dev = ctx.alloc_workspace(p, s), ctx.alloc_mask(p)
     ctx.build_mask(p, s, q, k, workspace=ws, mask=m_dev)                  # as the benchmark calls it
     _, sc_dev = ctx.build_mask(p, s, q, k, workspace=ws, mask=ctx.alloc_mask(p), want_score=True)
-    o_dev, lse_dev = ctx.sparse_attn(p, q, k, v, m_dev, want_lse=True)
+    o_dev, lse_dev = ctx.sparse_attn(p, q, k, v, m_dev, want_lse=True, workspace=ws)     # as the benchmark calls it
+    o_plain, lse_plain = ctx.sparse_attn(p, q, k, v, m_dev, want_lse=True)                # default work order
     od_dev, _ = ctx.full_attn(p, q, k, v)
     torch.cuda.synchronize()
+    assert torch.equal(o_dev, o_plain) and torch.equal(lse_dev, lse_plain), "the ranked work order changes the output"
+    del o_plain, lse_plain
     m_gpu = api.unpack_mask(m_dev, p.n_cols)
     sc_gpu = sc_dev.cpu().numpy()
     loc, nb = row_geometry(w.cu_seqlens, S)

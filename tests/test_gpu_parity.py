@@ -352,6 +352,37 @@ def test_one_call_entry_point_equals_two_calls(ctx, oracle):
     PU.check_output(o1.float().cpu().numpy(), o_ref, "one-call")
 
 
+def test_ranked_work_order_gives_identical_output(ctx, oracle):
+    """unisparse_sparse_attn_ws ranks the rows of every head by their number of selected blocks and changes nothing
+    but the order rows are worked on: output and LSE equal unisparse_sparse_attn bit for bit - packed ragged batches,
+    every head dimension and block size, grouped and ungrouped heads, a single row, a mask with an empty row - and
+    a workspace that is too small is refused."""
+    cases = [
+        dict(H=8, Hkv=2, lengths=(4096,), S=128, causal=True, d=128),
+        dict(H=4, Hkv=2, lengths=(300, 77, 1000, 0, 129), S=128, causal=True, d=128),
+        dict(H=3, Hkv=3, lengths=(640, 64), S=64, causal=False, d=128),
+        dict(H=4, Hkv=1, lengths=(100,), S=128, causal=True, d=128),
+        dict(H=4, Hkv=2, lengths=(900, 333), S=128, causal=True, d=256),
+        dict(H=4, Hkv=2, lengths=(900, 333), S=64, causal=False, d=64),
+    ]
+    for n, c in enumerate(cases):
+        w = W.random_small(H=c["H"], Hkv=c["Hkv"], lengths=c["lengths"], S=c["S"], causal=c["causal"], mode=W.TOP_P,
+                           param=0.7, seed=300 + n, d=c["d"])
+        q, k, v = PU.device_tensors(w)
+        p, s = PU.problem_of(w), PU.select_of(w)
+        m, _ = ctx.build_mask(p, s, q, k)
+        if n == 1:
+            m[1, 3] = 0                                        # an empty mask row among the others
+        ws = torch.empty(ctx.attn_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+        o1, l1 = ctx.sparse_attn(p, q, k, v, m, want_lse=True)
+        o2, l2 = ctx.sparse_attn(p, q, k, v, m, want_lse=True, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2) and torch.equal(l1, l2), f"case {n}"
+    with pytest.raises(api.UnisparseError) as e:
+        ctx.sparse_attn(p, q, k, v, m, workspace=torch.empty(64, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == 5
+
+
 def test_strided_views(ctx, oracle):
     """Q, K, V and O as views into larger buffers: padded token and head strides, non-zero storage offset."""
     w = W.random_small(H=4, Hkv=2, lengths=(256, 100), S=128, causal=True, mode=W.TOP_P, param=0.9, seed=19)
