@@ -196,7 +196,7 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
         for (int ks = 0; ks < C::KS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
     }
 
-    // ---- direct-to-LDS block loads: lane l of a 1 KB load fills row l / 16, physical chunk l % 16 -----
+    // ---- direct-to-LDS block loads: lane l of a 1 KB load fills row l / CH, physical chunk l % CH (CH = d / 8) ----
     // Issued as inline assembly so that the compiler does not serialise later LDS reads behind them; their
     // completion is awaited explicitly (vmcnt) before the barrier that publishes the buffer.
     const bf16_t *kptr = a.k.ptr + (int64_t)kvh * a.k.stride_head + tok0 * a.k.stride_tok;
@@ -209,12 +209,12 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
                      : "s"(gbase), "v"(goff), "s"(lds_addr)
                      : "memory", "m0");
     };
-    // Every wavefront issues kDma instructions of 1 KB (4 rows) for K and as many for V per block.
+    // Every wavefront issues kDma instructions of 1 KB (RPL rows) for K and as many for V per stage.
     constexpr int kDma = C::kDma;
-    // Per-lane byte offset of this lane's 16 bytes inside a block (row r, swizzled chunk) for the wavefront's
-    // first load; load number d of a block is 4 * NW rows further and that distance goes into the wave-uniform
-    // base address.  The K swizzle has a period of 16 rows: with 4 * NW = 8 the odd loads need an offset of
-    // their own (the V swizzle has a period of 4 rows).
+    // Per-lane byte offset of this lane's 16 bytes inside a stage (row r, swizzled chunk) for the wavefront's
+    // first load; load number d of a stage is d * RPL * NW rows further and that distance goes into the wave-uniform
+    // base address.  The K swizzle has a period of 16 rows: when the row step is 8 or 4, the loads need 2 or 4
+    // different offsets, used in turn (the V swizzle has a period of 4 rows, which every row step is a multiple of).
     constexpr int kRowStep = C::RPL * C::NW;      // rows between two consecutive loads of a wavefront
     constexpr int NKO = kRowStep % 16 == 0 ? 1 : (kRowStep % 8 == 0 ? 2 : 4);
     static_assert(kRowStep % 4 == 0, "the V swizzle repeats every four rows");
@@ -226,8 +226,8 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
             koff[o] = (uint32_t)(r * a.k.stride_tok + (dma_chunk ^ k_swizzle<D>(r + kRowStep * o)) * 8) * 2u;
         voff0 = (uint32_t)(r * a.v.stride_tok + (dma_chunk ^ v_swizzle<D>(r)) * 8) * 2u;
     }
-    // LDS map: K buffers at [0, 2 tiles), V buffers at [2 tiles, 4 tiles).  Instruction d of a block pair:
-    // d < kDma loads K rows of block jk into K buffer bk, d >= kDma loads V rows of block jv into V buffer bv.
+    // LDS map: K buffers at [0, 2 tiles), V buffers at [2 tiles, 4 tiles).  Instruction d of an iteration:
+    // d < kDma loads K rows of stage jk into K buffer bk, d >= kDma loads V rows of stage jv into V buffer bv.
     const int64_t k_step = (int64_t)kRowStep * a.k.stride_tok, v_step = (int64_t)kRowStep * a.v.stride_tok;
     const uint32_t lds_wave = lds_base + wave * 1024;
     auto dma_one = [&](int d, int jk, int bk, int jv, int bv) __attribute__((always_inline)) {
@@ -241,7 +241,7 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
         }
     };
 
-    // The same loads for a block that may be the shorter last one: rows beyond the sequence are replaced by its
+    // The same loads for a stage that may be the shorter last one: rows beyond the sequence are replaced by its
     // last row (only used outside the main loop, so the extra address arithmetic does not matter).
     auto dma_clamped = [&](int d, int jk, int bk, int jv, int bv) __attribute__((always_inline)) {
         const bool is_k = d < kDma;
@@ -265,8 +265,8 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
     float msc = -INFINITY;                       // m_run * c2 + kOff, or -inf while the row has seen no finite logit
     const float c2 = a.scale_log2;
     const int i16 = lane & 15;
-    static_assert(C::KB == 2, "the pipeline below works on two 32-key tiles per wavefront and block");
-    // The unit of the software pipeline is a "sub-step": one 32-key tile t of one block, numbered 2 n + t.
+    static_assert(C::KB == 2, "the pipeline below works on two 32-key tiles per wavefront and stage");
+    // The unit of the software pipeline is a "sub-step": one 32-key tile t of one stage, numbered 2 n + t.
     // State is kept twice, indexed by the parity of the sub-step (= t).
     f32x16 sacc[2];                              // S^T tile
     u32x4 pbw[2][2];                             // P^T tile as packed bf16 pairs: two MFMA operands of 16 keys
