@@ -64,7 +64,7 @@ typedef enum {
     UNISPARSE_ERR_SHAPE = 2,         /* c not dividing block_size, head counts, misaligned tensors ... */
     UNISPARSE_ERR_PARAM = 3,         /* threshold / budget outside (0, 1], unknown mode ... */
     UNISPARSE_ERR_UNSUPPORTED = 4,   /* valid request this build has no kernel for */
-    UNISPARSE_ERR_WORKSPACE = 5,     /* workspace smaller than unisparse_workspace_bytes() */
+    UNISPARSE_ERR_WORKSPACE = 5,     /* workspace smaller than the call's documented minimum */
     UNISPARSE_ERR_HIP = 6            /* HIP runtime reported an error */
 } unisparse_status;
 
@@ -128,7 +128,12 @@ const char *unisparse_status_string(unisparse_status s);
 size_t unisparse_mask_row_words(const unisparse_problem *p);             /* W                         */
 size_t unisparse_mask_words(const unisparse_problem *p);                 /* H * NQ * W  (uint64)      */
 size_t unisparse_score_elems(const unisparse_problem *p, const unisparse_select *s); /* (H/c_h)*NQ*NK floats */
+/* Workspace of unisparse_build_mask: _bytes() lets it run the fast form of the score computation (one sweep over
+ * the composite keys, with a sum per composite query row and key block parked in the workspace: S / c_q times the
+ * size of the scores; equal to _bytes_min() when that buffer would pass 8 GiB), _bytes_min() is the least it
+ * accepts (two sweeps, nothing parked). */
 size_t unisparse_workspace_bytes(const unisparse_problem *p, const unisparse_select *s);
+size_t unisparse_workspace_bytes_min(const unisparse_problem *p, const unisparse_select *s);
 
 /*
  * Sequence-level average pooling, Eq. (1): out[h][t'][:] = bf16( (1/c) * sum_{m<c} x[t'c + m][h][:] ),
@@ -165,7 +170,10 @@ unisparse_status unisparse_pool_seq_varlen(unisparse_ctx *ctx, const unisparse_p
 /*
  * Alg. 1 steps 1-4: composite tokens, compressed softmax scores, block aggregation, selection.
  *   Q : [T, H, d] view, K : [T, H_kv, d] view
- *   workspace : DEVICE scratch of at least unisparse_workspace_bytes() bytes, 256-byte aligned
+ *   workspace : DEVICE scratch of at least unisparse_workspace_bytes_min() bytes, 256-byte aligned.  With
+ *           unisparse_workspace_bytes() or more the scores are computed in one sweep over the composite keys,
+ *           below that in two; the two forms agree to rounding (both normalise by the same row sums, added in a
+ *           different order), so a score within a few ulp of the selection cut may fall on either side of it.
  *   M     : out, uint64 [H][NQ][W]
  *   score : out, optional (may be NULL), float [H / c_h][NQ][NK]; Score(i, j) of Eq. (3) for valid j,
  *           0 elsewhere.  When NULL the scores live in the workspace.
@@ -182,8 +190,9 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
  * serving loops, harnesses that forbid hipMalloc): the same kernels, with the composite tokens and the block
  * scores in a workspace that is part of the library's device image instead of a caller's buffer.  The call
  * allocates nothing and frees nothing.
- *   limit : unisparse_workspace_bytes(p, s) <= UNISPARSE_STATIC_WORKSPACE_BYTES (64 MiB; e.g. GQA 32/8 at
- *           32K tokens with c = 8 needs 48 MiB), else UNISPARSE_ERR_WORKSPACE and nothing is launched
+ *   limit : unisparse_workspace_bytes_min(p, s) <= UNISPARSE_STATIC_WORKSPACE_BYTES (64 MiB; e.g. GQA 32/8 at
+ *           32K tokens with c = 8 needs 48 MiB), else UNISPARSE_ERR_WORKSPACE and nothing is launched.  The
+ *           result is that of unisparse_build_mask with a workspace of UNISPARSE_STATIC_WORKSPACE_BYTES.
  *   M     : out, uint64 [H][NQ][W] as for unisparse_build_mask; the scores are not returned
  * Every device keeps one copy of that workspace for the life of the process, shared by all contexts and all
  * calls on the device: it holds the previous call's contents (nothing in it needs clearing - every value read is

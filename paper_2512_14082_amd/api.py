@@ -23,7 +23,8 @@ HEAD_DIM = 128
 
 EXPORTS = [
     "unisparse_create", "unisparse_destroy", "unisparse_status_string", "unisparse_mask_row_words",
-    "unisparse_mask_words", "unisparse_score_elems", "unisparse_workspace_bytes", "unisparse_avgpool_seq",
+    "unisparse_mask_words", "unisparse_score_elems", "unisparse_workspace_bytes", "unisparse_workspace_bytes_min",
+    "unisparse_avgpool_seq",
     "unisparse_pool_seq_varlen",
     "unisparse_build_mask", "unisparse_build_mask_static", "unisparse_select_blocks", "unisparse_sparse_attn",
     "unisparse_sparse_attn_ws", "unisparse_attn_workspace_bytes", "unisparse_full_attn",
@@ -75,7 +76,7 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     for name in ("unisparse_mask_row_words", "unisparse_mask_words", "unisparse_attn_workspace_bytes"):
         getattr(lib, name).argtypes = [PP]
         getattr(lib, name).restype = sz
-    for name in ("unisparse_score_elems", "unisparse_workspace_bytes"):
+    for name in ("unisparse_score_elems", "unisparse_workspace_bytes", "unisparse_workspace_bytes_min"):
         getattr(lib, name).argtypes = [PP, SP]
         getattr(lib, name).restype = sz
     lib.unisparse_avgpool_seq.argtypes = [vp, _Tensor, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp]
@@ -224,8 +225,14 @@ class Context:
         return torch.zeros((p.n_heads_q, p.n_rows, max(1, self.mask_row_words(p))), dtype=torch.int64,
                            device=f"cuda:{self.device}")
 
-    def alloc_workspace(self, p: Problem, s: Select) -> torch.Tensor:
-        return torch.empty(max(256, self.workspace_bytes(p, s)), dtype=torch.uint8, device=f"cuda:{self.device}")
+    def workspace_bytes_min(self, p: Problem, s: Select) -> int:
+        return int(self.lib.unisparse_workspace_bytes_min(p.c, s.c))
+
+    def alloc_workspace(self, p: Problem, s: Select, minimal: bool = False) -> torch.Tensor:
+        """Workspace of build_mask: the size that lets it compute the scores in one sweep, or (minimal) the least
+        it accepts."""
+        n = self.workspace_bytes_min(p, s) if minimal else self.workspace_bytes(p, s)
+        return torch.empty(max(256, n), dtype=torch.uint8, device=f"cuda:{self.device}")
 
     # ---- entry points --------------------------------------------------------------------------
     def avgpool_seq(self, x: torch.Tensor, c: int, layout: str = "htd") -> torch.Tensor:

@@ -11,8 +11,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libunisparse.so")
-SOURCES = ["attention_d256.hip", "attention.hip", "attention_d64.hip", "proxy.hip", "proxy_d64.hip", "proxy_d256.hip",
-           "pool.hip", "select.hip", "capi.hip"]
+SOURCES = ["attention_d256.hip", "attention.hip", "attention_d64.hip", "proxy.hip", "proxy_rowsums.hip", "proxy_d64.hip",
+           "proxy_rowsums_d64.hip", "proxy_d256.hip", "proxy_rowsums_d256.hip", "pool.hip", "select.hip", "capi.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
@@ -35,7 +35,7 @@ def _compile(src: str, extra) -> str:
 def build_library(extra_flags=(), verbose: bool = True) -> str:
     """Compile every HIP source for gfx950 and link the shared library.  Always recompiles."""
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)

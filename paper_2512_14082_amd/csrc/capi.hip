@@ -145,8 +145,14 @@ inline int64_t composite_offsets(const SeqTable &st, int c, int32_t *cu, bool *w
     return tot;
 }
 
+// The one-sweep score kernel leaves a sum per composite query row and key block: S / c_q times the size of Score
+// (key blocks rounded up to 64s).  It is used when that buffer stays below this size and the caller's workspace
+// holds it.
+constexpr size_t kRowSumsMaxBytes = (size_t)8 << 30;
+
 struct WsLayout {
-    size_t qt, kt, qth, kth, score, total;
+    size_t qt, kt, qth, kth, score, total;     // the two-sweep path
+    size_t u, wgt, total_rowsums;              // the one-sweep path in addition (total_rowsums = 0: not offered)
 };
 
 WsLayout carve(const unisparse_problem *p, const unisparse_select *s, const Geom &g, const HeadGeom &hg,
@@ -164,14 +170,23 @@ WsLayout carve(const unisparse_problem *p, const unisparse_select *s, const Geom
     w.kth = off; if (hg.kpool > 1) off += align256((size_t)hg.Hkc * Tk * row);
     w.score = off; if (need_score) off += align256((size_t)hg.Hc * g.NQ * g.NK * sizeof(float));
     w.total = off;
+    const size_t nq = (size_t)(p->block_size / s->c_q);
+    const size_t u_bytes = (size_t)hg.Hc * g.NQ * (((size_t)g.NK + 63) / 64 * 64) * nq * sizeof(float);
+    w.u = off; off += align256(u_bytes);
+    w.wgt = off; off += align256((size_t)hg.Hc * g.NQ * nq * sizeof(float));
+    w.total_rowsums = u_bytes <= kRowSumsMaxBytes ? off : 0;
     return w;
 }
 
 unisparse_status select_impl(const unisparse_problem *p, const unisparse_select *s, const Geom &g,
-                             const HeadGeom &hg, float *score, uint64_t *M, hipStream_t stream)
+                             const HeadGeom &hg, float *score, uint64_t *M, hipStream_t stream,
+                             const float *u = nullptr, const float *wgt = nullptr)
 {
     SelectArgs sa;
     sa.score = score;
+    sa.u = u;
+    sa.w = wgt;
+    sa.c_q = s->c_q;
     sa.mask = M;
     sa.st = g.st;
     sa.n_heads_c = hg.Hc;
@@ -296,6 +311,17 @@ size_t unisparse_workspace_bytes(const unisparse_problem *p, const unisparse_sel
     HeadGeom hg;
     if (check_problem(p, &g) != UNISPARSE_OK || check_select(p, s, &hg) != UNISPARSE_OK) return 0;
     // (also enough for unisparse_sparse_attn_ws, so that unisparse_attn can hand the same buffer on)
+    const WsLayout w = carve(p, s, g, hg, true);
+    const size_t build = w.total_rowsums != 0 ? w.total_rowsums : w.total;
+    const size_t attn = attention_sched_bytes(p->n_heads_q, p->n_heads_kv, g.NQ);
+    return (build > attn ? build : attn) + 256;
+}
+
+size_t unisparse_workspace_bytes_min(const unisparse_problem *p, const unisparse_select *s)
+{
+    Geom g;
+    HeadGeom hg;
+    if (check_problem(p, &g) != UNISPARSE_OK || check_select(p, s, &hg) != UNISPARSE_OK) return 0;
     const size_t build = carve(p, s, g, hg, true).total, attn = attention_sched_bytes(p->n_heads_q, p->n_heads_kv, g.NQ);
     return (build > attn ? build : attn) + 256;
 }
@@ -355,6 +381,7 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     unsigned char *base = reinterpret_cast<unsigned char *>(align256((size_t)(uintptr_t)workspace));
     const size_t lead = (size_t)(base - reinterpret_cast<unsigned char *>(workspace));
     if (workspace_bytes < w.total + lead) return UNISPARSE_ERR_WORKSPACE;
+    const bool rowsums = w.total_rowsums != 0 && workspace_bytes >= w.total_rowsums + lead;
     if ((st = enter(ctx)) != UNISPARSE_OK) return st;
     if (g.T == 0) return UNISPARSE_OK;
     hipStream_t stream = (hipStream_t)stream_;
@@ -405,8 +432,10 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     pa.NK = g.NK;
     pa.scale_log2 = scale_log2(p);
     pa.n_cu = ctx->n_cu;
+    pa.u = rowsums ? reinterpret_cast<float *>(base + w.u) : nullptr;
+    pa.w = rowsums ? reinterpret_cast<float *>(base + w.wgt) : nullptr;
     if (launch_proxy_scores(pa, stream) != hipSuccess) return UNISPARSE_ERR_HIP;
-    return select_impl(p, s, g, hg, sc, M, stream);
+    return select_impl(p, s, g, hg, sc, M, stream, pa.u, pa.w);
 }
 
 unisparse_status unisparse_build_mask_static(unisparse_ctx *ctx, const unisparse_problem *p,
@@ -414,7 +443,7 @@ unisparse_status unisparse_build_mask_static(unisparse_ctx *ctx, const unisparse
                                              uint64_t *M, void *stream)
 {
     if (ctx == nullptr) return UNISPARSE_ERR_NULL;
-    const size_t need = unisparse_workspace_bytes(p, s);      // 0 for an invalid problem: build_mask reports which
+    const size_t need = unisparse_workspace_bytes_min(p, s);  // 0 for an invalid problem: build_mask reports which
     if (need > (size_t)UNISPARSE_STATIC_WORKSPACE_BYTES) return UNISPARSE_ERR_WORKSPACE;
     return unisparse_build_mask(ctx, p, s, Q, K, ctx->scratch, (size_t)UNISPARSE_STATIC_WORKSPACE_BYTES, M, nullptr,
                                 stream);

@@ -122,7 +122,12 @@ hipError_t launch_avgpool_head(const bf16_t *x, int n_heads_in, int64_t tokens, 
 struct ProxyArgs {
     const bf16_t *qt;        // [Hc][Tq][d] composite queries (Tq = cu_cq[num_seqs])
     const bf16_t *kt;        // [Hkc][Tk][d] composite keys
-    float *score;            // [Hc][NQ][NK]
+    float *score;            // [Hc][NQ][NK], written by the two-sweep form (u == NULL)
+    // one-sweep form (u != NULL): per composite query row and key block the unnormalised sum of exponentials,
+    // [Hc][NQ][ceil(NK / 64)][n_q / 4][64][4] (row r of a query block and key block j at [j / 64][r / 4][j % 64][r % 4]),
+    // and the rows' weights 1 / denominator, [Hc][NQ][n_q]
+    float *u;
+    float *w;
     SeqTable st;
     int32_t cu_cq[kMaxSeqs + 1];     // packed offsets of the composite queries / keys: sequence b owns
     int32_t cu_ck[kMaxSeqs + 1];     // ceil(L_b / c) of them
@@ -138,7 +143,10 @@ struct ProxyArgs {
 hipError_t launch_proxy_scores(const ProxyArgs &a, hipStream_t stream);
 
 struct SelectArgs {
-    float *score;            // [Hc][NQ][NK]
+    float *score;            // [Hc][NQ][NK]: read, or - with u != NULL - formed from u and w and written
+    const float *u;          // ProxyArgs::u and ::w of the one-sweep score kernel, NULL = the scores are given
+    const float *w;
+    int32_t c_q;
     uint64_t *mask;          // [Hc * c_h][NQ][W]
     SeqTable st;
     int32_t n_heads_c;       // compressed heads

@@ -12,7 +12,7 @@ static int proxy_pick_hg(int G)
 
 hipError_t proxy_dispatch_d128(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream)
 {
-    return proxy_dispatch_t<128>(a, g, grid, stream);
+    return proxy_dispatch_t<128, false>(a, g, grid, stream);
 }
 
 hipError_t launch_proxy_scores(const ProxyArgs &a, hipStream_t stream)
@@ -39,10 +39,12 @@ hipError_t launch_proxy_scores(const ProxyArgs &a, hipStream_t stream)
     }
     if (nblk == 0) return hipSuccess;
     dim3 grid((unsigned)nblk);
+    const bool rowsums = a.u != nullptr;                    // one-sweep form: U and the row weights instead of Score
+    if (rowsums && a.w == nullptr) return hipErrorInvalidValue;
     switch (a.head_dim) {
-        case 64: return proxy_dispatch_d64(a, g, grid, stream);
-        case 128: return proxy_dispatch_d128(a, g, grid, stream);
-        case 256: return proxy_dispatch_d256(a, g, grid, stream);
+        case 64: return rowsums ? proxy_rowsums_dispatch_d64(a, g, grid, stream) : proxy_dispatch_d64(a, g, grid, stream);
+        case 128: return rowsums ? proxy_rowsums_dispatch_d128(a, g, grid, stream) : proxy_dispatch_d128(a, g, grid, stream);
+        case 256: return rowsums ? proxy_rowsums_dispatch_d256(a, g, grid, stream) : proxy_dispatch_d256(a, g, grid, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -5,7 +5,7 @@ namespace us {
 
 hipError_t proxy_dispatch_d256(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream)
 {
-    return proxy_dispatch_t<256>(a, g, grid, stream);
+    return proxy_dispatch_t<256, false>(a, g, grid, stream);
 }
 
 }  // namespace us

@@ -5,7 +5,7 @@ namespace us {
 
 hipError_t proxy_dispatch_d64(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream)
 {
-    return proxy_dispatch_t<64>(a, g, grid, stream);
+    return proxy_dispatch_t<64, false>(a, g, grid, stream);
 }
 
 }  // namespace us

@@ -6,10 +6,19 @@
 // x 64 rows, or fewer heads x more rows) and streams the composite keys through LDS in stages of
 // 128.  Each wavefront keeps its 64 query rows as MFMA B operands in registers and computes
 // 32-key x 64-query logit tiles transposed (S^T = K~ Q~^T, v_mfma_f32_32x32x16_bf16), so that every
-// lane owns whole query rows and the softmax statistics are lane-local.  Two sweeps over the
-// keys: the first finds a reference value and the denominator of each row, the second sums the normalised
-// probabilities over the composite keys of each key block (in registers), then over the
-// composite queries of each query block (cross-lane), and stores Score(i, j).
+// lane owns whole query rows and the softmax statistics are lane-local.
+//
+// Two forms.  The two-sweep form needs no memory beyond Score: the first sweep over the keys finds a reference value
+// and the denominator of each row, the second sums the normalised probabilities over the composite keys of each key
+// block (in registers), then over the composite queries of each query block (cross-lane), and stores Score(i, j).
+// The one-sweep form (ROWSUMS) halves the MFMA and exponential work: it writes, for every composite query row t and
+// key block j, the unnormalised sum U(t, j) of exp(P~(t, s) - ref_t) over the composite keys s of block j, and the
+// row's weight 1 / sum_j U(t, j); the selection kernel then forms Score(i, j) = sum_{t in block i} weight_t U(t, j)
+// as it loads its row.  ref_t is fixed by the first key tile and moves only when a tile's sum would pass 2^40; a
+// workgroup in which some row's reference moved after values had been written repeats the sweep with the final
+// references (the second sweep of the other form), so the common case costs one sweep and the worst case two.
+// U is laid out for the selection kernel's loads: per (head, query block) and per 64 key blocks, groups of four
+// composite query rows, each group 64 key blocks x 4 rows (a wavefront of the selection kernel reads 1 KB in a row).
 #pragma once
 #include "common.h"
 
@@ -55,7 +64,7 @@ struct ProxyGeom {
     int QT;          // 32-row MFMA tiles per wavefront: 2, or 1 to get twice the workgroups out of a small problem
 };
 
-template <int D, int NQB, int NKB, bool CAUSAL, int QT = 2>
+template <int D, int NQB, int NKB, bool CAUSAL, int QT = 2, bool ROWSUMS = false>
 __global__ __launch_bounds__(kPxThreads) __attribute__((amdgpu_waves_per_eu(PxCfg<D>::kWaves, PxCfg<D>::kWaves)))
 void proxy_kernel(ProxyArgs a, ProxyGeom g)
 {
@@ -157,6 +166,33 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
         wnorm[qb] = 0.0f;
     }
 
+    // Key blocks against the registers of a 32-key tile: register v of a lane holds key
+    // 8 (v / 4) + 4 lh + v % 4.  n_k >= 8: a block is one or more groups of 8 keys, summed
+    // over both lane halves; n_k = 4: a block is the four keys of one lane half; n_k = 64: a
+    // block is two tiles, the second tile adds to what the first one stored.
+    constexpr bool kHalfBlocks = NKB == 4, kTwoTiles = NKB == 64;
+    constexpr int NBK = kHalfBlocks ? 4 : (NKB >= 32 ? 1 : 32 / NKB);   // bins per lane
+    constexpr int GPB = kHalfBlocks ? 1 : (NKB >= 32 ? 4 : NKB / 8);    // register groups per bin
+
+    // one-sweep form: where this lane's rows go in U - element (row r of query block i, key block j) lives at
+    // [head][i][j / 64][r / 4][j % 64][r % 4] - and whether some row's reference moved after values relative to the
+    // old one had been stored.  Rows past the sequence's end (copies of its last row) fill the rest of a last,
+    // partial query block (they weigh 0) and have no place beyond it.
+    constexpr int kRowGroup = (NQB / 4) * 256;              // floats per 64 key blocks of one query block
+    float *ub[QT] = {};
+    bool row_ok[QT] = {};
+    bool moved = false;
+    if constexpr (ROWSUMS) {
+        const int64_t nk64 = (a.NK + 63) / 64;
+#pragma unroll
+        for (int qb = 0; qb < QT; ++qb) {
+            const int t = t0 + 32 * qb + lr, blk = t / NQB, r = t % NQB;
+            row_ok[qb] = blk < Nb;
+            ub[qb] = a.u + ((int64_t)head * a.NQ + row_base + blk) * nk64 * kRowGroup + (r / 4) * 256 + r % 4;
+        }
+    }
+    auto u_at = [&](int qb, int j) -> float & { return ub[qb][(j >> 6) * kRowGroup + (j & 63) * 4]; };
+
     // ---- per-tile work, as separate pieces so that the MFMAs of one tile can run under the VALU work of another
     // S^T of one 32-key tile for both query tiles (each K operand read feeds two MFMAs)
     auto mfma_tile = [&](f32x16 (&dst)[QT], const unsigned char *kb, int sub) __attribute__((always_inline)) {
@@ -215,13 +251,6 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
     // second sweep: normalised probabilities summed over the composite keys of each key block (registers),
     // then over the composite queries of each query block (lanes), stored as Score(i, j)
     auto bins_tile = [&](const f32x16 (&src)[QT], int s_lo, int sub) __attribute__((always_inline)) {
-        // Key blocks against the registers of a 32-key tile: register v of a lane holds key
-        // 8 (v / 4) + 4 lh + v % 4.  n_k >= 8: a block is one or more groups of 8 keys, summed
-        // over both lane halves; n_k = 4: a block is the four keys of one lane half; n_k = 64: a
-        // block is two tiles, the second tile adds to what the first one stored.
-        constexpr bool kHalfBlocks = NKB == 4, kTwoTiles = NKB == 64;
-        constexpr int NBK = kHalfBlocks ? 4 : (NKB >= 32 ? 1 : 32 / NKB);   // bins per lane
-        constexpr int GPB = kHalfBlocks ? 1 : (NKB >= 32 ? 4 : NKB / 8);    // register groups per bin
         constexpr int QR = NQB < 32 ? NQB : 32;                             // lanes of one query block
         float bin[QT][NBK];
 #pragma unroll
@@ -262,6 +291,98 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
             }
         }
     };
+    // one-sweep form: U(t, j) of one tile.  bin holds each lane's sums over its own keys of every block of the tile;
+    // the two lane halves of a row are added with one half swap per pair of blocks (the low half ends with the
+    // first block of the pair, the high half with the second).
+    auto store_rowsums = [&](const float (&bin)[QT][NBK], int s_lo, int sub) __attribute__((always_inline)) {
+#pragma unroll
+        for (int qb = 0; qb < QT; ++qb) {
+            if constexpr (kHalfBlocks) {
+#pragma unroll
+                for (int b = 0; b < NBK; ++b) {
+                    const int j = s_lo / 4 + 2 * b + lh;
+                    if (row_ok[qb] && j < Nb) u_at(qb, j) = bin[qb][b];
+                }
+            } else if constexpr (NBK >= 2) {
+#pragma unroll
+                for (int b = 0; b < NBK / 2; ++b) {
+                    auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(bin[qb][b]),
+                                                               __float_as_uint(bin[qb][b + NBK / 2]), false, false);
+                    const float x = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+                    const int j = s_lo / NKB + b + lh * (NBK / 2);
+                    if (row_ok[qb] && j < Nb) u_at(qb, j) = x;
+                }
+            } else {
+                const float x = bin[qb][0] + swap_half(bin[qb][0]);
+                const int j = s_lo / NKB;
+                if (row_ok[qb] && lh == 0 && j < Nb) {
+                    if (kTwoTiles && (sub & 1)) u_at(qb, j) += x;
+                    else u_at(qb, j) = x;
+                }
+            }
+        }
+    };
+    // one sweep: the exponentials of a tile relative to the row's reference feed both the denominator and U.  The
+    // reference is kept equal in the two lane halves of a row (their sums are added before they are stored), so
+    // the halves decide together whether it moves.
+    auto fused_tile = [&](const f32x16 (&src)[QT], int s_lo, int sub) __attribute__((always_inline)) {
+        constexpr float kBig = 1099511627776.0f;           // 2^40
+        float bin[QT][NBK], tsum[QT];
+        bool need[QT], redo = false;
+#pragma unroll
+        for (int qb = 0; qb < QT; ++qb) {
+#pragma unroll
+            for (int b = 0; b < NBK; ++b) bin[qb][b] = 0.0f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) bin[qb][(v >> 2) / GPB] += fast_exp2(fmaf(src[qb][v], c2, -mc[qb]));
+            tsum[qb] = bin[qb][0];
+#pragma unroll
+            for (int b = 1; b < NBK; ++b) tsum[qb] += bin[qb][b];
+            need[qb] = !(tsum[qb] <= kBig);
+            redo = redo || need[qb];
+        }
+        if (__any(redo)) {
+#pragma unroll
+            for (int qb = 0; qb < QT; ++qb) {
+                const bool nd = need[qb] || __shfl_xor((int)need[qb], 32, 64) != 0;
+                float mx = src[qb][0];
+#pragma unroll
+                for (int v = 1; v < 16; ++v) mx = fmaxf(mx, src[qb][v]);
+                mx = fmaxf(mx, swap_half(mx));
+                const float m_new = nd ? fmaxf(m_run[qb], mx) : m_run[qb];
+                const bool none = m_new == -INFINITY;      // nothing visible to this row yet
+                const float m_safe = none ? 0.0f : m_new;
+                const float alpha = fast_exp2((m_run[qb] - m_safe) * c2);
+                const float msc = m_safe * c2;
+                moved = moved || (nd && m_run[qb] != -INFINITY);
+#pragma unroll
+                for (int b = 0; b < NBK; ++b) bin[qb][b] = 0.0f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) bin[qb][(v >> 2) / GPB] += fast_exp2(fmaf(src[qb][v], c2, -msc));
+                tsum[qb] = bin[qb][0];
+#pragma unroll
+                for (int b = 1; b < NBK; ++b) tsum[qb] += bin[qb][b];
+                l_run[qb] *= alpha;
+                m_run[qb] = m_new;
+                mc[qb] = none ? -INFINITY : msc;
+            }
+        }
+#pragma unroll
+        for (int qb = 0; qb < QT; ++qb) l_run[qb] += tsum[qb];
+        store_rowsums(bin, s_lo, sub);
+    };
+    // the repeat sweep of the one-sweep form: U again, relative to the final references
+    auto rowsums_tile = [&](const f32x16 (&src)[QT], int s_lo, int sub) __attribute__((always_inline)) {
+        float bin[QT][NBK];
+#pragma unroll
+        for (int qb = 0; qb < QT; ++qb) {
+#pragma unroll
+            for (int b = 0; b < NBK; ++b) bin[qb][b] = 0.0f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) bin[qb][(v >> 2) / GPB] += fast_exp2(fmaf(src[qb][v], c2, -mc[qb]));
+        }
+        store_rowsums(bin, s_lo, sub);
+    };
     // Software pipeline over the tiles that every row of the wavefront sees in full: the MFMAs of a tile are
     // issued together with the VALU work of the tile before it (two sets of accumulators), across the stage
     // barriers.  sA holds the tile whose VALU work is still pending.
@@ -269,8 +390,13 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
     bool pend = false;
     int pend_slo = 0, pend_sub = 0;
     auto valu_tile = [&](const f32x16 (&src)[QT], auto pass_c, int s_lo, int sub) __attribute__((always_inline)) {
-        if constexpr (decltype(pass_c)::value == 0) stats_tile(src);
-        else bins_tile(src, s_lo, sub);
+        if constexpr (ROWSUMS) {
+            if constexpr (decltype(pass_c)::value == 0) fused_tile(src, s_lo, sub);
+            else rowsums_tile(src, s_lo, sub);
+        } else {
+            if constexpr (decltype(pass_c)::value == 0) stats_tile(src);
+            else bins_tile(src, s_lo, sub);
+        }
     };
     // one MFMA, its share of the VALU work, one operand read per two MFMAs - a hint for the machine scheduler
     constexpr int MIXV = 4;
@@ -286,8 +412,10 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
         }
     };
 
+    bool repeat = true;
     static_for<2>([&](auto pass_c) __attribute__((always_inline)) {
         constexpr int pass = decltype(pass_c)::value;
+        if (ROWSUMS && pass == 1 && !repeat) return;        // (uniform over the workgroup)
         load_stage(0);
         __syncthreads();                                    // previous sweep finished reading LDS
         store_stage(0);
@@ -361,26 +489,32 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
                 mc[qb] = m_t * c2;
                 // rows beyond the sequence (clamped copies of its last row) must not count in a partial query block
                 wnorm[qb] = t0 + 32 * qb + lr < Lq ? 1.0f / l_t : 0.0f;
+                if constexpr (ROWSUMS) {        // [head][query block][row]
+                    const int t = t0 + 32 * qb + lr;
+                    if (wave_active && lh == 0 && row_ok[qb])
+                        a.w[((int64_t)head * a.NQ + row_base + t / NQB) * NQB + t % NQB] = wnorm[qb];
+                }
             }
+            if constexpr (ROWSUMS) repeat = __syncthreads_or(moved ? 1 : 0) != 0;
         }
     });
 }
 
-template <int D, int NQB, int NKB, int QT = 2>
+template <int D, int NQB, int NKB, int QT, bool ROWSUMS>
 static hipError_t proxy_launch_t(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream)
 {
     const int lds_bytes = 2 * PxCfg<D>::kStageBytes;
     hipError_t e;
     if (a.causal) {
         static LdsAttr attr;
-        e = attr.set(reinterpret_cast<const void *>(&proxy_kernel<D, NQB, NKB, true, QT>), lds_bytes);
+        e = attr.set(reinterpret_cast<const void *>(&proxy_kernel<D, NQB, NKB, true, QT, ROWSUMS>), lds_bytes);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((proxy_kernel<D, NQB, NKB, true, QT>), grid, dim3(kPxThreads), lds_bytes, stream, a, g);
+        hipLaunchKernelGGL((proxy_kernel<D, NQB, NKB, true, QT, ROWSUMS>), grid, dim3(kPxThreads), lds_bytes, stream, a, g);
     } else {
         static LdsAttr attr;
-        e = attr.set(reinterpret_cast<const void *>(&proxy_kernel<D, NQB, NKB, false, QT>), lds_bytes);
+        e = attr.set(reinterpret_cast<const void *>(&proxy_kernel<D, NQB, NKB, false, QT, ROWSUMS>), lds_bytes);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((proxy_kernel<D, NQB, NKB, false, QT>), grid, dim3(kPxThreads), lds_bytes, stream, a, g);
+        hipLaunchKernelGGL((proxy_kernel<D, NQB, NKB, false, QT, ROWSUMS>), grid, dim3(kPxThreads), lds_bytes, stream, a, g);
     }
     return hipGetLastError();
 }
@@ -389,16 +523,16 @@ static hipError_t proxy_launch_t(const ProxyArgs &a, const ProxyGeom &g, dim3 gr
 // blocks of at most 32 composite tokens (high compression ratios).
 constexpr bool proxy_has_single_tile(int head_dim, int nqb) { return head_dim == 128 && nqb <= 32; }
 
-// All granularities of one head dimension; each head dimension is compiled in a translation unit of its own.
-template <int D>
+// All granularities of one head dimension and one form; each pair is compiled in a translation unit of its own.
+template <int D, bool ROWSUMS>
 static hipError_t proxy_dispatch_t(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream)
 {
     const int nq = a.S / a.c_q, nk = a.S / a.c_k;
-#define US_PX(NQB, NKB)                                                                  \
-    if (nq == NQB && nk == NKB) {                                                        \
-        if constexpr (proxy_has_single_tile(D, NQB))                                     \
-            if (g.QT == 1) return proxy_launch_t<D, NQB, NKB, 1>(a, g, grid, stream);    \
-        return proxy_launch_t<D, NQB, NKB>(a, g, grid, stream);                          \
+#define US_PX(NQB, NKB)                                                                           \
+    if (nq == NQB && nk == NKB) {                                                                 \
+        if constexpr (proxy_has_single_tile(D, NQB))                                              \
+            if (g.QT == 1) return proxy_launch_t<D, NQB, NKB, 1, ROWSUMS>(a, g, grid, stream);    \
+        return proxy_launch_t<D, NQB, NKB, 2, ROWSUMS>(a, g, grid, stream);                       \
     }
     US_PX(4, 4); US_PX(4, 8); US_PX(4, 16); US_PX(4, 32); US_PX(4, 64);
     US_PX(8, 4); US_PX(8, 8); US_PX(8, 16); US_PX(8, 32); US_PX(8, 64);
@@ -409,8 +543,12 @@ static hipError_t proxy_dispatch_t(const ProxyArgs &a, const ProxyGeom &g, dim3 
     return hipErrorInvalidValue;
 }
 
+// two-sweep form (Score written by the kernel) and one-sweep form (U and the row weights written) per head dimension
 hipError_t proxy_dispatch_d64(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream);
 hipError_t proxy_dispatch_d128(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream);
 hipError_t proxy_dispatch_d256(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream);
+hipError_t proxy_rowsums_dispatch_d64(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream);
+hipError_t proxy_rowsums_dispatch_d128(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream);
+hipError_t proxy_rowsums_dispatch_d256(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream);
 
 }  // namespace us

@@ -13,6 +13,9 @@
 // One wavefront owns one (compressed head, query-block row): lane l holds scores l, l + 64, l + 128, ... in
 // registers, so the mask word w of the row is exactly the 64-lane ballot of "element w of my registers is kept".
 // Sums are fp64, as in the definition.  The kept columns are written once per head of the broadcast group.
+//
+// The scores are either given, or (FROM_ROWSUMS) formed here from what the one-sweep score kernel left: Eq. (3) as
+// Score(i, j) = sum over the composite query rows t of block i of weight_t U(t, j), in ascending t, and stored.
 #include "common.h"
 
 namespace us {
@@ -65,7 +68,7 @@ __device__ __forceinline__ int wave_sum(int x)
 }
 
 // E = register elements per lane: rows of up to 64 E valid blocks.
-template <int E>
+template <int E, bool FROM_ROWSUMS>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
 {
     const int lane = threadIdx.x & 63;
@@ -79,6 +82,26 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
     const int ne = (nv + 63) >> 6;                        // register elements in use (uniform), <= E
 
     float *srow = a.score + ((int64_t)hc * a.NQ + row) * a.NK;
+    float agg[FROM_ROWSUMS ? E : 1];
+    if constexpr (FROM_ROWSUMS) {
+        // the block's n_q composite query rows in groups of four: per group and 64 key blocks, 1 KB in lane order
+        const int nq4 = a.S / a.c_q / 4;
+        const float *ur = a.u + ((int64_t)hc * a.NQ + row) * ((a.NK + 63) / 64) * (nq4 * 256) + lane * 4;
+        const float *wr = a.w + ((int64_t)hc * a.NQ + row) * (nq4 * 4);
+#pragma unroll
+        for (int e = 0; e < E; ++e) agg[e] = 0.0f;
+#pragma unroll 2
+        for (int c = 0; c < nq4; ++c) {
+            const f32x4 w4 = *reinterpret_cast<const f32x4 *>(wr + 4 * c);
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                if (e < ne && lane + 64 * e < nv) {
+                    const f32x4 u4 = *reinterpret_cast<const f32x4 *>(ur + (e * nq4 + c) * 256);
+                    agg[e] = fmaf(w4[3], u4[3], fmaf(w4[2], u4[2], fmaf(w4[1], u4[1], fmaf(w4[0], u4[0], agg[e]))));
+                }
+            }
+        }
+    }
     uint32_t sb[E];                                       // score bits (non-negative floats order like integers)
     double sd[E];
     double local = 0.0;
@@ -89,7 +112,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
         sd[e] = 0.0;
         if (e < ne) {
             const int idx = lane + 64 * e;
-            float s = idx < nv ? srow[idx] : 0.0f;
+            float s;
+            if constexpr (FROM_ROWSUMS) {
+                s = idx < nv ? agg[e] : 0.0f;
+                if (idx < nv) srow[idx] = s;
+            } else {
+                s = idx < nv ? srow[idx] : 0.0f;
+            }
             s = s > 0.0f ? s : 0.0f;
             sb[e] = __float_as_uint(s);
             sd[e] = (double)s;
@@ -211,10 +240,15 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t stream)
     const int64_t n = (int64_t)a.n_heads_c * a.NQ;
     if (n == 0) return hipSuccess;
     if (a.NK > UNISPARSE_MAX_BLOCKS_PER_SEQ) return hipErrorInvalidValue;
+    if (a.u != nullptr && (a.w == nullptr || a.c_q < 1 || a.S % a.c_q != 0 || (a.S / a.c_q) % 4 != 0)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((n + kSelRows - 1) / kSelRows)), block(kSelThreads);
     const int ne = (a.NK + 63) / 64;
-#define US_SEL(EE) \
-    if (ne <= EE) { hipLaunchKernelGGL(select_kernel<EE>, grid, block, 0, stream, a); return hipGetLastError(); }
+#define US_SEL(EE)                                                                               \
+    if (ne <= EE) {                                                                              \
+        if (a.u != nullptr) hipLaunchKernelGGL((select_kernel<EE, true>), grid, block, 0, stream, a);  \
+        else hipLaunchKernelGGL((select_kernel<EE, false>), grid, block, 0, stream, a);          \
+        return hipGetLastError();                                                                \
+    }
     US_SEL(1) US_SEL(2) US_SEL(4) US_SEL(8) US_SEL(16) US_SEL(32) US_SEL(64)
 #undef US_SEL
     return hipErrorInvalidValue;

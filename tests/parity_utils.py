@@ -118,28 +118,33 @@ def full_pipeline_check(ctx, oracle, w: W.Workload, layout="htd", check_dense=Tr
                                               None if w.rand_q is None else w.rand_q[h, off[b]:off[b + 1]])
                               for b in range(len(w.cu_seqlens) - 1)])
         assert np.array_equal(qt_bits[h], W.f32_to_bf16_bits(ref)), f"pooling mismatch head {h}"
-    # -- scores and mask
-    m_dev, sc_dev = ctx.build_mask(p, s, q, k, layout, want_score=True)
-    torch.cuda.synchronize()
-    m_gpu = api.unpack_mask(m_dev, p.n_cols)
-    sc_gpu = sc_dev.cpu().numpy()
+    # -- scores and mask, in both forms of the score computation: two sweeps over the composite keys (the least
+    #    workspace), then one sweep (the workspace the size query asks for); the latter's mask feeds the attention
     m_ref, sc_ref = oracle.build_mask(qf, kf, w.cu_seqlens, w.block_size, w.c_q, w.c_k, w.causal, w.mode, param,
                                       c_h=w.c_h, rows=rows, pool=w.pool, rand=rand_of(w))
     rr = slice(None) if rows is None else list(rows)
-    np.testing.assert_allclose(sc_gpu[:, rr], sc_ref[:, rr], rtol=score_rtol, atol=1e-6)
-    # -- the score kernel's two tilings (one or two 32-row tiles per wavefront) do the same arithmetic per row
-    if w.head_dim == 128 and w.block_size // w.c_q <= 32:
-        for tiles in (1, 2):
-            s_t = select_of(w)
-            s_t.proxy_tiles = tiles
-            m_t, sc_t = ctx.build_mask(p, s_t, q, k, layout, want_score=True)
-            torch.cuda.synchronize()
-            assert torch.equal(sc_t, sc_dev) and torch.equal(m_t, m_dev), f"proxy_tiles={tiles} changes the result"
-    agree = check_mask_against_oracle(m_gpu, m_ref, sc_ref, w.cu_seqlens, w.block_size, w.causal, w.mode, param, rows)
-    # -- selection alone is index work: on the GPU's own scores it must match the oracle bit for bit
-    m_sel = oracle.select_mask(sc_gpu, w.cu_seqlens, w.block_size, w.causal, w.mode, param, rows)
-    m_sel = np.repeat(m_sel, w.c_h, axis=0)
-    assert np.array_equal(m_gpu[:, rr], m_sel[:, rr]), "selection differs from the oracle on identical scores"
+    assert ctx.workspace_bytes(p, s) > ctx.workspace_bytes_min(p, s)
+    for minimal in (True, False):
+        form = "two sweeps" if minimal else "one sweep"
+        ws = ctx.alloc_workspace(p, s, minimal=minimal)
+        m_dev, sc_dev = ctx.build_mask(p, s, q, k, layout, workspace=ws, want_score=True)
+        torch.cuda.synchronize()
+        m_gpu = api.unpack_mask(m_dev, p.n_cols)
+        sc_gpu = sc_dev.cpu().numpy()
+        np.testing.assert_allclose(sc_gpu[:, rr], sc_ref[:, rr], rtol=score_rtol, atol=1e-6, err_msg=form)
+        # -- the score kernel's two tilings (one or two 32-row tiles per wavefront) do the same arithmetic per row
+        if w.head_dim == 128 and w.block_size // w.c_q <= 32:
+            for tiles in (1, 2):
+                s_t = select_of(w)
+                s_t.proxy_tiles = tiles
+                m_t, sc_t = ctx.build_mask(p, s_t, q, k, layout, workspace=ws, want_score=True)
+                torch.cuda.synchronize()
+                assert torch.equal(sc_t, sc_dev) and torch.equal(m_t, m_dev), f"{form}: proxy_tiles={tiles} changes the result"
+        agree = check_mask_against_oracle(m_gpu, m_ref, sc_ref, w.cu_seqlens, w.block_size, w.causal, w.mode, param, rows)
+        # -- selection alone is index work: on the GPU's own scores it must match the oracle bit for bit
+        m_sel = oracle.select_mask(sc_gpu, w.cu_seqlens, w.block_size, w.causal, w.mode, param, rows)
+        m_sel = np.repeat(m_sel, w.c_h, axis=0)
+        assert np.array_equal(m_gpu[:, rr], m_sel[:, rr]), f"{form}: selection differs from the oracle on identical scores"
     # -- sparse attention on the GPU's own mask
     o_dev, lse_dev = ctx.sparse_attn(p, q, k, v, m_dev, layout, want_lse=True)
     torch.cuda.synchronize()
@@ -232,6 +237,24 @@ def sampled_config_check(ctx, oracle, w: W.Workload, seed, n_random=16, attn_hea
     say(f"{w.name}: mask agreement {agree:.6f} over {counts[1]} sampled decisions ({counts[0]} admissible mismatches)")
     assert agree >= MASK_AGREE_MIN, f"mask agreement {agree:.5f}"
     result = {"agreement": agree, "density": density, "densities": {w.param: density}}
+    # -- the other form of the score computation (two sweeps, the least workspace) on the same sampled rows
+    m2_dev, sc2_dev = ctx.build_mask(p, s, q, k, workspace=ctx.alloc_workspace(p, s, minimal=True), want_score=True)
+    torch.cuda.synchronize()
+    m2, sc2 = api.unpack_mask(m2_dev, p.n_cols), sc2_dev.cpu().numpy()
+    del m2_dev, sc2_dev
+    assert np.array_equal(m2, oracle.select_mask(sc2, w.cu_seqlens, S, w.causal, w.mode, w.param)), \
+        "two sweeps: selection differs from the oracle on identical scores"
+    cnt2 = [0, 0]
+    for h in range(H):
+        rows, sc_ref = ref[h]
+        np.testing.assert_allclose(sc2[h, rows], sc_ref[0, rows], rtol=2e-3, atol=1e-6)
+        m_ref = oracle.select_mask(sc_ref, w.cu_seqlens, S, w.causal, w.mode, w.param, rows)
+        check_mask_against_oracle(m2[h:h + 1], m_ref, sc_ref, w.cu_seqlens, S, w.causal, w.mode, w.param, rows, cnt2)
+    agree2 = 1.0 - cnt2[0] / cnt2[1]
+    between = float((m2 == m_gpu).mean())
+    say(f"{w.name}: two-sweep form: mask agreement {agree2:.6f} with the oracle, {between:.6f} of all bits equal to the one-sweep mask")
+    assert agree2 >= MASK_AGREE_MIN and between >= MASK_AGREE_MIN
+    del m2, sc2
     # -- further thresholds on the same score buffer (selection only)
     for P in extra_thresholds:
         s_p = select_of(w)

@@ -92,6 +92,30 @@ def test_attention_with_steep_logits_other_head_dims(ctx, oracle, d, kind, S, ca
     steep_logits_check(ctx, oracle, kind, S, causal, d)
 
 
+@pytest.mark.parametrize("kind", ["rising", "falling", "spikes", "ramp"])
+@pytest.mark.parametrize("S,causal,cq,ck,d", [(128, True, 8, 8, 128), (128, False, 8, 8, 128), (64, True, 4, 4, 128),
+                                              (128, True, 32, 32, 128), (128, True, 4, 16, 64), (128, False, 16, 2, 256)])
+def test_scores_with_logits_spanning_hundreds_of_units(ctx, oracle, kind, S, causal, cq, ck, d):
+    """The compressed-space softmax on the same inputs, in both forms of the score kernel.  The one-sweep form
+    stores sums of exponentials relative to a per-row reference that is fixed early and moves only when a tile's sum
+    would pass 2^40: "rising" moves it after values were stored (the workgroup then repeats its sweep), "spikes" and
+    "ramp" move it inside a tile and from tile to tile, "falling" makes later terms vanish against the first."""
+    w = W.steep_logits(kind, H=4, Hkv=2, lengths=(8 * S + 40, 3 * S), S=S, causal=causal, seed=170 + S + cq, d=d)
+    w.c_q, w.c_k, w.mode, w.param = cq, ck, W.TOP_P, 0.9
+    q, k, _ = PU.device_tensors(w)
+    qf, kf, _ = w.f32()
+    p, s = PU.problem_of(w), PU.select_of(w)
+    m_ref, sc_ref = oracle.build_mask(qf, kf, w.cu_seqlens, S, cq, ck, causal, w.mode, w.param)
+    for minimal in (True, False):
+        m_dev, sc_dev = ctx.build_mask(p, s, q, k, workspace=ctx.alloc_workspace(p, s, minimal=minimal), want_score=True)
+        torch.cuda.synchronize()
+        m_gpu, sc_gpu = api.unpack_mask(m_dev, p.n_cols), sc_dev.cpu().numpy()
+        assert np.isfinite(sc_gpu).all()
+        np.testing.assert_allclose(sc_gpu, sc_ref, rtol=2e-3, atol=1e-6, err_msg=f"minimal={minimal}")
+        PU.check_mask_against_oracle(m_gpu, m_ref, sc_ref, w.cu_seqlens, S, causal, w.mode, w.param)
+        assert np.array_equal(m_gpu, oracle.select_mask(sc_gpu, w.cu_seqlens, S, causal, w.mode, w.param))
+
+
 def steep_logits_check(ctx, oracle, kind, S, causal, d):
     """Rows whose logits differ by up to ~190 natural-log units: the attention kernels keep one reference value per
     row for their exponentials and move it only when a probability would grow past a bound, so these inputs drive

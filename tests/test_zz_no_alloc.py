@@ -1,6 +1,6 @@
 """unisparse_build_mask_static (the entry point for callers that cannot allocate): same mask as
-unisparse_build_mask, bit for bit, on two calls in a row, the second on a smaller problem; too large a
-problem is refused."""
+unisparse_build_mask (given a buffer of the static workspace's size), bit for bit, on calls in a row, each on a
+smaller problem than the one before; too large a problem is refused."""
 import numpy as np
 import pytest
 import torch
@@ -18,11 +18,15 @@ def test_static_workspace_entry_point_matches_build_mask():
     first = W.gqa_planted(L=8192, H=8, Hkv=2, S=128, P=0.9, seed=71)
     second = W.random_small(H=4, Hkv=2, lengths=(300, 77, 1000), S=128, causal=True, mode=W.TOP_K, param=0.3, seed=72)
     second.c_q, second.c_k, second.c_h = 16, 4, 2
-    for w in (first, second):
+    # (the largest first: at 32K tokens x 32 heads only the two-sweep form of the score computation fits the static
+    # workspace, the two smaller problems run the one-sweep form; build_mask makes the same choice for a 64 MiB buffer)
+    largest = W.gqa_planted(L=32768, H=32, Hkv=8, S=128, P=0.95, seed=70)
+    for w in (largest, first, second):
         q, k, _ = PU.device_tensors(w)
         p, s = PU.problem_of(w), PU.select_of(w)
-        assert ctx.workspace_bytes(p, s) <= 64 << 20
-        m_ref, _ = ctx.build_mask(p, s, q, k)
+        assert ctx.workspace_bytes_min(p, s) <= 64 << 20
+        assert (ctx.workspace_bytes(p, s) > 64 << 20) == (w is largest)
+        m_ref, _ = ctx.build_mask(p, s, q, k, workspace=torch.empty(64 << 20, dtype=torch.uint8, device="cuda"))
         m = ctx.alloc_mask(p)
         m.fill_(-1)
         torch.cuda.synchronize()
@@ -35,7 +39,7 @@ def test_static_workspace_entry_point_matches_build_mask():
     # a problem whose workspace exceeds the static one is refused before anything is launched
     big = api.Problem([0, 131072], 32, 8, 128, True)
     s = api.Select()
-    assert ctx.workspace_bytes(big, s) > 64 << 20
+    assert ctx.workspace_bytes_min(big, s) > 64 << 20
     dummy = torch.empty((1, 128, 128), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(api.UnisparseError) as e:
         ctx.build_mask_static(big, s, dummy, dummy, torch.zeros(8, dtype=torch.int64, device="cuda"))
