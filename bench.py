@@ -199,7 +199,9 @@ def main():
                    "gain": w.gain, "layout": lay},
         "speedup_vs_dense": ms_dense / ms_step,
         "mask_density": nnz / valid,
-        "kernels_ms": {"pool": ms_pool, "proxy_scores": ms_build - ms_pool - ms_select, "select": ms_select,
+        # (scores_and_select: the one-sweep score kernel plus the selection kernel that normalises its row sums;
+        #  select_given_scores: unisparse_select_blocks alone on a score buffer, for reference)
+        "kernels_ms": {"pool": ms_pool, "scores_and_select": ms_build - ms_pool, "select_given_scores": ms_select,
                        "build_mask": ms_build, "sparse_attn": ms_sparse, "dense_attn": ms_dense},
         "effective_tflops": valid * flop_pair / (ms_step * 1e-3) / 1e12,
         "dense_tflops": dense_tflops,

@@ -130,8 +130,8 @@ size_t unisparse_mask_words(const unisparse_problem *p);                 /* H * 
 size_t unisparse_score_elems(const unisparse_problem *p, const unisparse_select *s); /* (H/c_h)*NQ*NK floats */
 /* Workspace of unisparse_build_mask: _bytes() lets it run the fast form of the score computation (one sweep over
  * the composite keys, with a sum per composite query row and key block parked in the workspace: S / c_q times the
- * size of the scores; equal to _bytes_min() when that buffer would pass 8 GiB), _bytes_min() is the least it
- * accepts (two sweeps, nothing parked). */
+ * size of the scores; equal to _bytes_min() when that buffer would pass 8 GiB or when S / c_k < 8, where the sums
+ * would cost what they save), _bytes_min() is the least it accepts (two sweeps, nothing parked). */
 size_t unisparse_workspace_bytes(const unisparse_problem *p, const unisparse_select *s);
 size_t unisparse_workspace_bytes_min(const unisparse_problem *p, const unisparse_select *s);
 

@@ -146,8 +146,8 @@ inline int64_t composite_offsets(const SeqTable &st, int c, int32_t *cu, bool *w
 }
 
 // The one-sweep score kernel leaves a sum per composite query row and key block: S / c_q times the size of Score
-// (key blocks rounded up to 64s).  It is used when that buffer stays below this size and the caller's workspace
-// holds it.
+// (key blocks rounded up to 64s).  It is used when that buffer stays below this size, a key block holds at least 8
+// composite keys and the caller's workspace holds it.
 constexpr size_t kRowSumsMaxBytes = (size_t)8 << 30;
 
 struct WsLayout {
@@ -174,7 +174,9 @@ WsLayout carve(const unisparse_problem *p, const unisparse_select *s, const Geom
     const size_t u_bytes = (size_t)hg.Hc * g.NQ * (((size_t)g.NK + 63) / 64 * 64) * nq * sizeof(float);
     w.u = off; off += align256(u_bytes);
     w.wgt = off; off += align256((size_t)hg.Hc * g.NQ * nq * sizeof(float));
-    w.total_rowsums = u_bytes <= kRowSumsMaxBytes ? off : 0;
+    // (with 4 composite keys per key block the sums are a quarter of the exponentials: writing and reading them
+    // costs what the second sweep does)
+    w.total_rowsums = u_bytes <= kRowSumsMaxBytes && p->block_size / s->c_k >= 8 ? off : 0;
     return w;
 }
 

@@ -72,6 +72,7 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
     constexpr int kPxPitch = C::kPitch, kPxStageBytes = C::kStageBytes, kHeadDim = D;
     constexpr int kPxRowsPerWave = 32 * QT;                // shadows the two-tile default
     static_assert(QT == 2 || NQB <= 32, "a query block must stay inside one wavefront");
+    static_assert(!ROWSUMS || NKB >= 8, "the one-sweep form is not offered for key blocks of 4 composite keys");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -297,13 +298,7 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
     auto store_rowsums = [&](const float (&bin)[QT][NBK], int s_lo, int sub) __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QT; ++qb) {
-            if constexpr (kHalfBlocks) {
-#pragma unroll
-                for (int b = 0; b < NBK; ++b) {
-                    const int j = s_lo / 4 + 2 * b + lh;
-                    if (row_ok[qb] && j < Nb) u_at(qb, j) = bin[qb][b];
-                }
-            } else if constexpr (NBK >= 2) {
+            if constexpr (NBK >= 2) {
 #pragma unroll
                 for (int b = 0; b < NBK / 2; ++b) {
                     auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(bin[qb][b]),
@@ -528,11 +523,13 @@ template <int D, bool ROWSUMS>
 static hipError_t proxy_dispatch_t(const ProxyArgs &a, const ProxyGeom &g, dim3 grid, hipStream_t stream)
 {
     const int nq = a.S / a.c_q, nk = a.S / a.c_k;
-#define US_PX(NQB, NKB)                                                                           \
-    if (nq == NQB && nk == NKB) {                                                                 \
-        if constexpr (proxy_has_single_tile(D, NQB))                                              \
-            if (g.QT == 1) return proxy_launch_t<D, NQB, NKB, 1, ROWSUMS>(a, g, grid, stream);    \
-        return proxy_launch_t<D, NQB, NKB, 2, ROWSUMS>(a, g, grid, stream);                       \
+#define US_PX(NQB, NKB)                                                                               \
+    if constexpr (!ROWSUMS || NKB >= 8) {                                                             \
+        if (nq == NQB && nk == NKB) {                                                                 \
+            if constexpr (proxy_has_single_tile(D, NQB))                                              \
+                if (g.QT == 1) return proxy_launch_t<D, NQB, NKB, 1, ROWSUMS>(a, g, grid, stream);    \
+            return proxy_launch_t<D, NQB, NKB, 2, ROWSUMS>(a, g, grid, stream);                       \
+        }                                                                                             \
     }
     US_PX(4, 4); US_PX(4, 8); US_PX(4, 16); US_PX(4, 32); US_PX(4, 64);
     US_PX(8, 4); US_PX(8, 8); US_PX(8, 16); US_PX(8, 32); US_PX(8, 64);

@@ -123,7 +123,8 @@ def full_pipeline_check(ctx, oracle, w: W.Workload, layout="htd", check_dense=Tr
     m_ref, sc_ref = oracle.build_mask(qf, kf, w.cu_seqlens, w.block_size, w.c_q, w.c_k, w.causal, w.mode, param,
                                       c_h=w.c_h, rows=rows, pool=w.pool, rand=rand_of(w))
     rr = slice(None) if rows is None else list(rows)
-    assert ctx.workspace_bytes(p, s) > ctx.workspace_bytes_min(p, s)
+    # (the one-sweep form is offered when a key block holds at least 8 composite keys; else both runs are two sweeps)
+    assert (ctx.workspace_bytes(p, s) > ctx.workspace_bytes_min(p, s)) == (w.block_size // w.c_k >= 8)
     for minimal in (True, False):
         form = "two sweeps" if minimal else "one sweep"
         ws = ctx.alloc_workspace(p, s, minimal=minimal)
