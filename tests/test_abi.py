@@ -51,6 +51,29 @@ def test_status_strings_and_size_queries_without_gpu():
     assert lib.unisparse_mask_words(bad.c) == 0
 
 
+def test_the_two_workspace_sizes_of_build_mask():
+    """unisparse_workspace_bytes adds room for one float per (composite query row, key block) - S / c_q times the
+    scores, key blocks rounded up to 64 - where the one-sweep score computation is offered: key blocks of at least 8
+    composite keys and a buffer of at most 8 GiB.  Elsewhere the two queries agree."""
+    lib = api.load_library()
+    full = lambda p, s: lib.unisparse_workspace_bytes(p.c, s.c)
+    least = lambda p, s: lib.unisparse_workspace_bytes_min(p.c, s.c)
+    p = api.Problem([0, 32768], 32, 8, 128, True)                 # 256 blocks, 4096 composite rows per head at c = 8
+    s = api.Select()
+    rowsums = 32 * 256 * 256 * 16 * 4
+    assert 0 < least(p, s) < full(p, s)
+    assert rowsums <= full(p, s) - least(p, s) <= rowsums + 32 * 256 * 16 * 4 + 1024
+    s4 = api.Select(c_q=8, c_k=32)                                # 4 composite keys per key block
+    assert full(p, s4) == least(p, s4) > 0
+    s2 = api.Select(c_q=32, c_k=2, c_h=2)                         # 4 rows per query block, compressed heads: a quarter ...
+    assert full(p, s2) - least(p, s2) >= 16 * 256 * 256 * 4 * 4   # ... of half as many scores
+    ragged = api.Problem([0, 100, 8300], 8, 2, 128, True)         # 1 + 65 blocks: key blocks rounded up to 128
+    assert full(ragged, s) - least(ragged, s) >= 8 * 66 * 128 * 16 * 4
+    huge = api.Problem([0, 524288], 32, 8, 128, True)             # 34 GB of row sums: not offered
+    assert full(huge, s) == least(huge, s) > 0
+    assert least(api.Problem([0, 100], 8, 3, 128, True), s) == 0  # invalid problem
+
+
 def test_head_dimensions_and_pooling_options_in_the_size_queries():
     lib = api.load_library()
     s = api.Select(c_h=2)
