@@ -114,6 +114,10 @@ typedef struct {
                                         library (2, or 1 when the problem yields few workgroups: high compression
                                         ratios, compressed heads); 1 or 2 force it.  1 exists for head_dim 128 and
                                         block_size / c_q <= 32 (UNISPARSE_ERR_UNSUPPORTED otherwise) */
+    int32_t query_pool_pass;         /* tuning: 0 = the score kernel pools the queries itself as it loads them (Eq. (1)
+                                        on the fly, the same arithmetic; done for average pooling without head
+                                        compression), 1 = always in a pass of their own, as the keys are */
+    int32_t reserved;                /* must be 0 */
     const float *rand_q;             /* UNISPARSE_POOL_STOCHASTIC only (else ignored): DEVICE uniform numbers in [0, 1), */
     const float *rand_k;             /* one per composite token: rand_q [H][sum_b ceil(L_b/c_q)],
                                         rand_k [H_kv][sum_b ceil(L_b/c_k)], laid out like the composite tokens.

@@ -51,7 +51,8 @@ class _Tensor(ctypes.Structure):
 class _Select(ctypes.Structure):
     _fields_ = [("c_q", ctypes.c_int32), ("c_k", ctypes.c_int32), ("c_h", ctypes.c_int32), ("mode", ctypes.c_int32),
                 ("threshold", ctypes.c_double), ("budget_frac", ctypes.c_double), ("pool", ctypes.c_int32),
-                ("proxy_tiles", ctypes.c_int32), ("rand_q", ctypes.c_void_p), ("rand_k", ctypes.c_void_p)]
+                ("proxy_tiles", ctypes.c_int32), ("query_pool_pass", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("rand_q", ctypes.c_void_p), ("rand_k", ctypes.c_void_p)]
 
 
 _lib = None
@@ -155,11 +156,13 @@ class Select:
     rand_q: Optional[torch.Tensor] = None   # stochastic pooling: float32 device uniforms [H, composite queries]
     rand_k: Optional[torch.Tensor] = None   # and [H_kv, composite keys]
     proxy_tiles: int = 0   # tuning of the score kernel: 0 = automatic, 1 / 2 = 32-row tiles per wavefront
+    query_pool_pass: int = 0   # tuning: 0 = queries pooled inside the score kernel where possible, 1 = in their own pass
 
     @property
     def c(self):
         self._c = _Select(self.c_q, self.c_k, self.c_h, self.mode, float(self.threshold), float(self.budget_frac),
-                          self.pool, self.proxy_tiles, _rand_ptr(self.rand_q), _rand_ptr(self.rand_k))
+                          self.pool, self.proxy_tiles, self.query_pool_pass, 0, _rand_ptr(self.rand_q),
+                          _rand_ptr(self.rand_k))
         return ctypes.byref(self._c)
 
 

@@ -89,6 +89,7 @@ unisparse_status check_select(const unisparse_problem *p, const unisparse_select
     if (s->mode != UNISPARSE_TOP_P && s->mode != UNISPARSE_TOP_K) return UNISPARSE_ERR_PARAM;
     if (s->pool < UNISPARSE_POOL_AVG || s->pool > UNISPARSE_POOL_STOCHASTIC) return UNISPARSE_ERR_PARAM;
     if (s->proxy_tiles < 0 || s->proxy_tiles > 2) return UNISPARSE_ERR_PARAM;
+    if (s->query_pool_pass < 0 || s->query_pool_pass > 1 || s->reserved != 0) return UNISPARSE_ERR_PARAM;
     if (s->proxy_tiles == 1 && (p->head_dim != 128 || nq > 32)) return UNISPARSE_ERR_UNSUPPORTED;
     if (s->pool == UNISPARSE_POOL_STOCHASTIC && (s->rand_q == nullptr || s->rand_k == nullptr)) return UNISPARSE_ERR_NULL;
     if (s->mode == UNISPARSE_TOP_P && !(s->threshold > 0.0 && s->threshold <= 1.0)) return UNISPARSE_ERR_PARAM;
@@ -397,9 +398,12 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
     // windows never straddle sequences; with whole windows everywhere the packed batch pools as one flat array
     const bool stoch = s->pool == UNISPARSE_POOL_STOCHASTIC;
     const int d = p->head_dim;
-    hipError_t pe = stoch     ? launch_stochpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, d, s->rand_q, qt, stream)
-                    : whole_q ? launch_avgpool_seq(view(Q), p->n_heads_q, g.T, s->c_q, s->pool, d, qt, stream)
-                              : launch_avgpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, s->pool, d, qt, stream);
+    // averaged queries that no head pooling follows are formed by the score kernel as it loads them
+    const bool q_on_the_fly = s->pool == UNISPARSE_POOL_AVG && s->c_h == 1 && s->query_pool_pass == 0;
+    hipError_t pe = q_on_the_fly ? hipSuccess
+                    : stoch      ? launch_stochpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, d, s->rand_q, qt, stream)
+                    : whole_q    ? launch_avgpool_seq(view(Q), p->n_heads_q, g.T, s->c_q, s->pool, d, qt, stream)
+                                 : launch_avgpool_seq_varlen(view(Q), p->n_heads_q, g.st, s->c_q, s->pool, d, qt, stream);
     if (pe != hipSuccess) return UNISPARSE_ERR_HIP;
     pe = stoch     ? launch_stochpool_seq_varlen(view(K), p->n_heads_kv, g.st, s->c_k, d, s->rand_k, kt, stream)
          : whole_k ? launch_avgpool_seq(view(K), p->n_heads_kv, g.T, s->c_k, s->pool, d, kt, stream)
@@ -418,7 +422,8 @@ unisparse_status unisparse_build_mask(unisparse_ctx *ctx, const unisparse_proble
         }
     }
     float *sc = score != nullptr ? score : reinterpret_cast<float *>(base + w.score);
-    pa.qt = qt;
+    pa.qt = q_on_the_fly ? nullptr : qt;
+    pa.q_src = view(Q);
     pa.kt = kt;
     pa.score = sc;
     pa.st = g.st;

@@ -78,6 +78,24 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x)
     return u >> 16;
 }
 
+// 8 bf16 (16 bytes) -> fp32, and back with round to nearest even.
+__device__ __forceinline__ void unpack8(const u32x4 &w, float *f)
+{
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f[2 * e] = __uint_as_float(w[e] << 16);
+        f[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+}
+
+__device__ __forceinline__ u32x4 pack8_rne(const float *f)
+{
+    u32x4 w;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = f32_to_bf16_rne(f[2 * e]) | (f32_to_bf16_rne(f[2 * e + 1]) << 16);
+    return w;
+}
+
 // Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{}).
 template <typename F, int... I>
 __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
@@ -120,7 +138,8 @@ hipError_t launch_avgpool_head(const bf16_t *x, int n_heads_in, int64_t tokens, 
                                hipStream_t stream);
 
 struct ProxyArgs {
-    const bf16_t *qt;        // [Hc][Tq][d] composite queries (Tq = cu_cq[num_seqs])
+    const bf16_t *qt;        // [Hc][Tq][d] composite queries (Tq = cu_cq[num_seqs]); NULL: q_src is pooled on the fly
+    TensorView q_src;        // the queries themselves, [T, H, d] view (used when qt == NULL: average pooling, Eq. (1))
     const bf16_t *kt;        // [Hkc][Tk][d] composite keys
     float *score;            // [Hc][NQ][NK], written by the two-sweep form (u == NULL)
     // one-sweep form (u != NULL): per composite query row and key block the unnormalised sum of exponentials,

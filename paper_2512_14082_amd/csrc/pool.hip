@@ -10,23 +10,6 @@
 
 namespace us {
 
-__device__ __forceinline__ void unpack8(const u32x4 &w, float *f)
-{
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        f[2 * e] = __uint_as_float(w[e] << 16);
-        f[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
-    }
-}
-
-__device__ __forceinline__ u32x4 pack8_rne(const float *f)
-{
-    u32x4 w;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) w[e] = f32_to_bf16_rne(f[2 * e]) | (f32_to_bf16_rne(f[2 * e + 1]) << 16);
-    return w;
-}
-
 template <int C>
 __global__ __launch_bounds__(256) void avgpool_seq_kernel(const bf16_t *__restrict__ x, int64_t stride_tok,
                                                           int64_t stride_head, int64_t tokens_out, int c_rt,

@@ -134,9 +134,46 @@ void proxy_kernel(ProxyArgs a, ProxyGeom g)
     for (int qb = 0; qb < QT; ++qb) {
         int t = min(t0 + 32 * qb + lr, Lq - 1);
         lim_row[qb] = limit_of(t);
-        const bf16_t *src = a.qt + ((int64_t)head * Tq + a.cu_cq[seq] + t) * kHeadDim + 8 * lh;
+        if (a.qt != nullptr) {                              // (uniform) composite queries pooled by an earlier pass
+            const bf16_t *src = a.qt + ((int64_t)head * Tq + a.cu_cq[seq] + t) * kHeadDim + 8 * lh;
 #pragma unroll
-        for (int ks = 0; ks < C::kSteps; ++ks) qreg[qb][ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
+            for (int ks = 0; ks < C::kSteps; ++ks) qreg[qb][ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
+        } else {
+            // Eq. (1) on the fly, the arithmetic of the pooling kernel: fp32 sum of the window's tokens in token
+            // order (the sequence's last window may be short), one division, one rounding to bf16
+            const int cnt = min(a.c_q, Lb - t * a.c_q);
+            const bf16_t *src = a.q_src.ptr + (int64_t)head * a.q_src.stride_head +
+                                ((int64_t)tok0 + (int64_t)t * a.c_q) * a.q_src.stride_tok + 8 * lh;
+            float acc[C::kSteps][8];
+#pragma unroll
+            for (int ks = 0; ks < C::kSteps; ++ks)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[ks][e] = 0.0f;
+#pragma unroll 2
+            for (int m = 0; m < a.c_q; ++m) {
+                if (m < cnt) {
+                    u32x4 w[C::kSteps];
+#pragma unroll
+                    for (int ks = 0; ks < C::kSteps; ++ks)
+                        w[ks] = *reinterpret_cast<const u32x4 *>(src + (int64_t)m * a.q_src.stride_tok + 16 * ks);
+#pragma unroll
+                    for (int ks = 0; ks < C::kSteps; ++ks) {
+                        float f[8];
+                        unpack8(w[ks], f);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[ks][e] += f[e];
+                    }
+                }
+            }
+            const float cf = (float)cnt;
+#pragma unroll
+            for (int ks = 0; ks < C::kSteps; ++ks) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[ks][e] = acc[ks][e] / cf;
+                const u32x4 pk = pack8_rne(acc[ks]);
+                qreg[qb][ks] = __builtin_bit_cast(bf16x8, pk);
+            }
+        }
     }
 
     const bf16_t *kbase = a.kt + ((int64_t)kvh * Tk + a.cu_ck[seq]) * kHeadDim;

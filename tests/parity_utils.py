@@ -141,6 +141,14 @@ def full_pipeline_check(ctx, oracle, w: W.Workload, layout="htd", check_dense=Tr
                 m_t, sc_t = ctx.build_mask(p, s_t, q, k, layout, workspace=ws, want_score=True)
                 torch.cuda.synchronize()
                 assert torch.equal(sc_t, sc_dev) and torch.equal(m_t, m_dev), f"{form}: proxy_tiles={tiles} changes the result"
+        # -- averaged queries are pooled inside the score kernel unless head pooling follows: the same arithmetic as
+        #    the pooling pass (checked bit for bit above), so the same scores as with that pass forced
+        if w.pool == 0 and w.c_h == 1:
+            s_p = select_of(w)
+            s_p.query_pool_pass = 1
+            m_p, sc_p = ctx.build_mask(p, s_p, q, k, layout, workspace=ws, want_score=True)
+            torch.cuda.synchronize()
+            assert torch.equal(sc_p, sc_dev) and torch.equal(m_p, m_dev), f"{form}: pooling the queries on the fly changes the result"
         agree = check_mask_against_oracle(m_gpu, m_ref, sc_ref, w.cu_seqlens, w.block_size, w.causal, w.mode, param, rows)
         # -- selection alone is index work: on the GPU's own scores it must match the oracle bit for bit
         m_sel = oracle.select_mask(sc_gpu, w.cu_seqlens, w.block_size, w.causal, w.mode, param, rows)
@@ -205,6 +213,12 @@ def sampled_config_check(ctx, oracle, w: W.Workload, seed, n_random=16, attn_hea
     torch.cuda.synchronize()
     assert torch.equal(o_dev, o_plain) and torch.equal(lse_dev, lse_plain), "the ranked work order changes the output"
     del o_plain, lse_plain
+    s_p = select_of(w)
+    s_p.query_pool_pass = 1                 # the queries pooled in a pass of their own instead of inside the score kernel
+    m_p, sc_p = ctx.build_mask(p, s_p, q, k, workspace=ws, want_score=True)
+    torch.cuda.synchronize()
+    assert torch.equal(sc_p, sc_dev) and torch.equal(m_p, m_dev), "pooling the queries on the fly changes the result"
+    del m_p, sc_p
     m_gpu = api.unpack_mask(m_dev, p.n_cols)
     sc_gpu = sc_dev.cpu().numpy()
     loc, nb = row_geometry(w.cu_seqlens, S)

@@ -88,7 +88,7 @@ def test_head_dimensions_and_pooling_options_in_the_size_queries():
     assert lib.unisparse_workspace_bytes(p.c, api.Select(pool=1).c) > 0
     assert lib.unisparse_workspace_bytes(p.c, api.Select(pool=2).c) == 0     # stochastic pooling without its uniforms
     assert lib.unisparse_workspace_bytes(p.c, api.Select(pool=7).c) == 0
-    assert ctypes.sizeof(api._Select) == 56                        # four ints, two doubles, two ints, two pointers
+    assert ctypes.sizeof(api._Select) == 64                        # four ints, two doubles, four ints, two pointers
 
 
 def test_null_arguments_are_refused_before_any_device_work():
