@@ -251,6 +251,8 @@ unisparse_status unisparse_full_attn(unisparse_ctx *ctx, const unisparse_problem
 /*
  * The paper's one-call interface (Sec. 5): build_mask followed by sparse_attn_ws (which reuses the workspace) on
  * the same stream.
+ *   workspace : as for unisparse_build_mask (at least unisparse_workspace_bytes_min(); unisparse_workspace_bytes()
+ *               for the one-sweep score computation); both sizes cover the row ranking of sparse_attn_ws
  *   M : scratch/out uint64 [H][NQ][W] (the mask that was used, left for inspection)
  */
 unisparse_status unisparse_attn(unisparse_ctx *ctx, const unisparse_problem *p, const unisparse_select *s,
