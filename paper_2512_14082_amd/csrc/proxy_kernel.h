@@ -6,7 +6,9 @@
 // x 64 rows, or fewer heads x more rows) and streams the composite keys through LDS in stages of
 // 128.  Each wavefront keeps its 64 query rows as MFMA B operands in registers and computes
 // 32-key x 64-query logit tiles transposed (S^T = K~ Q~^T, v_mfma_f32_32x32x16_bf16), so that every
-// lane owns whole query rows and the softmax statistics are lane-local.
+// lane owns whole query rows and the softmax statistics are lane-local.  The query rows are read as composite tokens
+// or, since each of them is used by exactly one wavefront, formed from the queries themselves as they are loaded
+// (Eq. (1), average pooling; ProxyArgs::qt == NULL).
 //
 // Two forms.  The two-sweep form needs no memory beyond Score: the first sweep over the keys finds a reference value
 // and the denominator of each row, the second sums the normalised probabilities over the composite keys of each key
