@@ -72,6 +72,10 @@ def test_the_two_workspace_sizes_of_build_mask():
     huge = api.Problem([0, 524288], 32, 8, 128, True)             # 34 GB of row sums: not offered
     assert full(huge, s) == least(huge, s) > 0
     assert least(api.Problem([0, 100], 8, 3, 128, True), s) == 0  # invalid problem
+    assert full(p, api.Select(query_pool_pass=1)) == full(p, s)   # a tuning knob, no effect on the sizes
+    assert full(p, api.Select(query_pool_pass=2)) == 0            # out of range
+    bad = api._Select(8, 8, 1, 0, 0.9, 0.25, 0, 0, 0, 7, None, None)     # reserved field not zero
+    assert lib.unisparse_workspace_bytes(ctypes.byref(p._c), ctypes.byref(bad)) == 0
 
 
 def test_head_dimensions_and_pooling_options_in_the_size_queries():
