@@ -477,6 +477,43 @@ def test_randomised_small_problems(ctx, oracle):
                                  f"mode={mode} param={param} pool={pool} {layout}: {e}") from e
 
 
+def test_randomised_medium_problems(ctx, oracle):
+    """Twenty-four seeded problems of 2K-14K tokens per sequence (many key stages per sweep of the score kernel, several
+    workgroups per head, all head dimensions), a third of them with logits that rise, fall, spike or ramp over hundreds
+    of units; scores, mask and attention against the oracle on sampled query-block rows."""
+    for it in range(24):
+        rng = np.random.default_rng(52000 + it)
+        d = int(rng.choice([128, 128, 64, 256]))
+        S = int(rng.choice([64, 128]))
+        cs = [c for c in (2, 4, 8, 16, 32) if S // c in (4, 8, 16, 32, 64)]
+        cq, ck = int(rng.choice(cs)), int(rng.choice(cs))
+        Hkv, G = int(rng.choice([1, 2])), int(rng.choice([1, 2, 4]))
+        H = Hkv * G
+        ch = int(rng.choice([1, 1] + [c for c in (1, 2, 4) if H % c == 0 and (G % c == 0 or c % G == 0)]))
+        nseq = int(rng.integers(1, 4))
+        lengths = tuple(int(x) for x in rng.integers(2000, 14000, nseq))
+        causal = bool(rng.random() < 0.7)
+        mode = W.TOP_P if rng.random() < 0.6 else W.TOP_K
+        param = float(rng.choice([0.5, 0.8, 0.9, 0.95] if mode == W.TOP_P else [0.1, 0.25, 0.5]))
+        layout = str(rng.choice(["htd", "thd"]))
+        kind = str(rng.choice(["random", "random", "rising", "spikes", "ramp", "falling"]))
+        if kind == "random":
+            w = W.random_small(H=H, Hkv=Hkv, lengths=lengths, S=S, causal=causal, mode=mode, param=param,
+                               seed=2900 + it, scale=float(rng.choice([0.5, 1.0, 1.5])), d=d)
+        else:
+            step = float(rng.choice([2.0, 8.0, 16.0])) / (max(lengths) // S / 8 + 1)
+            w = W.steep_logits(kind, H=H, Hkv=Hkv, lengths=lengths, S=S, causal=causal, seed=2900 + it, d=d, step=step)
+            w.mode, w.param = mode, param
+        w.c_q, w.c_k, w.c_h = cq, ck, ch
+        NQ = sum(-(-L // S) for L in lengths)
+        rows = sorted(set(int(x) for x in rng.integers(0, NQ, 5)) | {NQ - 1, 0})
+        try:
+            PU.full_pipeline_check(ctx, oracle, w, layout=layout, check_dense=(it % 4 == 0), rows=rows)
+        except AssertionError as e:
+            raise AssertionError(f"draw {it}: {kind} d={d} S={S} c=({cq},{ck},{ch}) H={H}/{Hkv} lengths={lengths} "
+                                 f"causal={causal} mode={mode} param={param} {layout} rows={rows}: {e}") from e
+
+
 @pytest.mark.parametrize("d", [64, 256])
 @pytest.mark.parametrize("S,lengths,cq,ck,ch,causal,mode,param,pool,layout", [
     (128, (512, 384), 8, 8, 1, True, W.TOP_P, 0.9, 0, "htd"),
