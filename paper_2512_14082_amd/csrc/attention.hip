@@ -62,14 +62,16 @@ __global__ __launch_bounds__(kRankThreads) void attn_rank_kernel(AttnArgs a, Att
 
 size_t attention_sched_bytes(int n_heads_q, int n_heads_kv, int NQ)
 {
-    // the larger of the two chunk shapes the launcher may pick
+    // the largest of the chunk shapes the launcher may pick: 32 or 64 workgroups of 1 or 2 heads
     size_t best = 0;
-    for (int HG = 1; HG <= 2; ++HG) {
-        if ((n_heads_q / n_heads_kv) % HG != 0) continue;
-        const int R = 32 / HG;
-        const int64_t n_chunks = (int64_t)((NQ + R - 1) / R) * (n_heads_q / HG);
-        const int64_t nblk = (n_chunks + kNumXcd - 1) / kNumXcd * kNumXcd * 32;
-        if ((size_t)nblk * 4 > best) best = (size_t)nblk * 4;
+    for (int chunk = 32; chunk <= 64; chunk += 32) {
+        for (int HG = 1; HG <= 2; ++HG) {
+            if ((n_heads_q / n_heads_kv) % HG != 0) continue;
+            const int R = chunk / HG;
+            const int64_t n_chunks = (int64_t)((NQ + R - 1) / R) * (n_heads_q / HG);
+            const int64_t nblk = (n_chunks + kNumXcd - 1) / kNumXcd * kNumXcd * chunk;
+            if ((size_t)nblk * 4 > best) best = (size_t)nblk * 4;
+        }
     }
     return (best + 255) & ~(size_t)255;
 }

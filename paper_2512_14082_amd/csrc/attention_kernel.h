@@ -36,12 +36,12 @@
 
 namespace us {
 
-template <int S, int D>
+template <int S, int D, int SKP>
 struct AttnCfg {
     static constexpr int RB = 2 * D;               // bytes of a K or V row
     static constexpr int CH = D / 8;               // 16-byte chunks per row
-    static constexpr int SK = D == 256 ? 64 : S;   // keys per stage: what one iteration of the pipeline works on and
-                                                   // what an LDS buffer holds (half a block of 128 at d = 256)
+    static constexpr int SK = SKP;                 // keys per stage: what one iteration of the pipeline works on and
+                                                   // what an LDS buffer holds (a block, or half a block of 128)
     static constexpr int SPB = S / SK;             // stages per block
     static constexpr int QW = S / 32;              // query slices of 32 rows
     static constexpr int KW = SK / 64;             // key groups of 64 rows
@@ -91,11 +91,12 @@ struct AttnOrder {
 };
 constexpr int kRankMaxRows = 8192;      // rows per head the rank kernel sorts (in LDS)
 
-template <int D, int S, bool CAUSAL, bool DENSE>
-__global__ __launch_bounds__((AttnCfg<S, D>::NT)) __attribute__((amdgpu_waves_per_eu(AttnCfg<S, D>::kWaves, AttnCfg<S, D>::kWaves)))
+template <int D, int S, bool CAUSAL, bool DENSE, int SKP>
+__global__ __launch_bounds__((AttnCfg<S, D, SKP>::NT))
+__attribute__((amdgpu_waves_per_eu(AttnCfg<S, D, SKP>::kWaves, AttnCfg<S, D, SKP>::kWaves)))
 void attention_kernel(AttnArgs a, AttnOrder ord)
 {
-    using C = AttnCfg<S, D>;
+    using C = AttnCfg<S, D, SKP>;
     constexpr int SK = C::SK, RB = C::RB;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     __shared__ uint16_t jlist[UNISPARSE_MAX_BLOCKS_PER_SEQ];
@@ -697,18 +698,21 @@ void attention_kernel(AttnArgs a, AttnOrder ord)
 // fills a.sched with the ranked work order of `ord` (defined in attention.hip)
 hipError_t launch_attention_rank(const AttnArgs &a, const AttnOrder &ord, hipStream_t stream);
 
-template <int D, int S, bool CAUSAL, bool DENSE>
+template <int D, int S, bool CAUSAL, bool DENSE, int SKP>
 static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
 {
-    using C = AttnCfg<S, D>;
+    using C = AttnCfg<S, D, SKP>;
     static LdsAttr attr;
-    hipError_t e = attr.set(reinterpret_cast<const void *>(&attention_kernel<D, S, CAUSAL, DENSE>), C::kLdsBytes);
+    hipError_t e = attr.set(reinterpret_cast<const void *>(&attention_kernel<D, S, CAUSAL, DENSE, SKP>), C::kLdsBytes);
     if (e != hipSuccess) return e;
     if (a.n_heads_q == 0 || a.NQ == 0) return hipSuccess;
     const int G = a.n_heads_q / a.n_heads_kv;
+    // workgroups of a chunk: what an XCD (32 CUs) runs at a time - two per CU with the half-block stages of d = 128
+    // (four wavefronts and 64 KB of LDS each)
+    constexpr int kChunk = (D == 128 && S == 128 && SKP == 64) ? 64 : 32;
     AttnOrder ord;
     ord.HG = G % 2 == 0 ? 2 : 1;
-    ord.R = 32 / ord.HG;
+    ord.R = kChunk / ord.HG;
     ord.n_rg = (a.NQ + ord.R - 1) / ord.R;
     ord.n_chunks = ord.n_rg * (a.n_heads_q / ord.HG);
     ord.head_major = 0;
@@ -718,7 +722,7 @@ static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
                         (int64_t)attention_sched_bytes(a.n_heads_q, a.n_heads_kv, a.NQ) <= a.sched_bytes;
     if (ranked && a.W >= 16) {
         ord.HG = 1;
-        ord.R = 32;
+        ord.R = kChunk;
         ord.n_rg = (a.NQ + ord.R - 1) / ord.R;
         ord.n_chunks = ord.n_rg * a.n_heads_q;
     }
@@ -729,7 +733,7 @@ static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
         if (e != hipSuccess) return e;
         ord.table = a.sched;
     }
-    hipLaunchKernelGGL((attention_kernel<D, S, CAUSAL, DENSE>), dim3((unsigned)nblk), dim3(C::NT), C::kLdsBytes, stream,
+    hipLaunchKernelGGL((attention_kernel<D, S, CAUSAL, DENSE, SKP>), dim3((unsigned)nblk), dim3(C::NT), C::kLdsBytes, stream,
                        a, ord);
     return hipGetLastError();
 }
@@ -739,10 +743,25 @@ template <int D>
 static hipError_t attn_dispatch_t(const AttnArgs &a, hipStream_t stream)
 {
     const bool dense = a.mask == nullptr;
-#define US_AT(SS, CA, DE) \
-    if (a.S == SS && (a.causal != 0) == CA && dense == DE) return attn_launch_t<D, SS, CA, DE>(a, stream)
-    US_AT(128, true, true); US_AT(128, true, false); US_AT(128, false, true); US_AT(128, false, false);
-    US_AT(64, true, true); US_AT(64, true, false); US_AT(64, false, true); US_AT(64, false, false);
+    // Stage size at S = 128.  d = 256: half a block (a whole one would need 256 KB of LDS).  d = 128: half a block -
+    // workgroups of four wavefronts, two per CU, which fill each other's barriers, prologues and epilogues (dense
+    // -2 %, block-sparse rows of up to a few hundred blocks -2 ... -3 %) - except for block-sparse rows of a thousand
+    // blocks and more, where whole blocks and one workgroup of eight wavefronts per CU do better (twice as many
+    // workgroups per XCD spread over more of the K/V stream than its L2 holds).
+    constexpr int kHalf = 64;
+    const bool whole_blocks = D != 256 && (D != 128 || (!dense && a.W >= 16));
+#define US_AT(SS, CA, DE, SK) \
+    if (a.S == SS && (a.causal != 0) == CA && dense == DE) return attn_launch_t<D, SS, CA, DE, SK>(a, stream)
+    if (whole_blocks) {
+        if constexpr (D != 256) {
+            US_AT(128, true, true, 128); US_AT(128, true, false, 128); US_AT(128, false, true, 128); US_AT(128, false, false, 128);
+        }
+    } else {
+        if constexpr (D != 64) {
+            US_AT(128, true, true, kHalf); US_AT(128, true, false, kHalf); US_AT(128, false, true, kHalf); US_AT(128, false, false, kHalf);
+        }
+    }
+    US_AT(64, true, true, 64); US_AT(64, true, false, 64); US_AT(64, false, true, 64); US_AT(64, false, false, 64);
 #undef US_AT
     return hipErrorInvalidValue;
 }
