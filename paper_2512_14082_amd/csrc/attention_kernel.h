@@ -707,9 +707,9 @@ static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
     if (e != hipSuccess) return e;
     if (a.n_heads_q == 0 || a.NQ == 0) return hipSuccess;
     const int G = a.n_heads_q / a.n_heads_kv;
-    // workgroups of a chunk: what an XCD (32 CUs) runs at a time - two per CU with the half-block stages of d = 128
-    // (four wavefronts and 64 KB of LDS each)
-    constexpr int kChunk = (D == 128 && S == 128 && SKP == 64) ? 64 : 32;
+    // workgroups of a chunk: what an XCD (32 CUs) runs at a time - two per CU with the half-block stages of d = 64
+    // and 128 (four wavefronts and at most 64 KB of LDS each)
+    constexpr int kChunk = (D <= 128 && S == 128 && SKP == 64) ? 64 : 32;
     AttnOrder ord;
     ord.HG = G % 2 == 0 ? 2 : 1;
     ord.R = kChunk / ord.HG;
@@ -743,23 +743,22 @@ template <int D>
 static hipError_t attn_dispatch_t(const AttnArgs &a, hipStream_t stream)
 {
     const bool dense = a.mask == nullptr;
-    // Stage size at S = 128.  d = 256: half a block (a whole one would need 256 KB of LDS).  d = 128: half a block -
-    // workgroups of four wavefronts, two per CU, which fill each other's barriers, prologues and epilogues (dense
-    // -2 %, block-sparse rows of up to a few hundred blocks -2 ... -3 %) - except for block-sparse rows of a thousand
-    // blocks and more, where whole blocks and one workgroup of eight wavefronts per CU do better (twice as many
-    // workgroups per XCD spread over more of the K/V stream than its L2 holds).
+    // Stage size at S = 128.  d = 256: half a block (a whole one would need 256 KB of LDS).  d = 64 and 128: half a
+    // block - workgroups of four wavefronts, two per CU, which fill each other's barriers, prologues and epilogues
+    // (d = 128: dense -2 %, block-sparse rows of up to a few hundred blocks -2 ... -4 %; d = 64: -4 % and -8 %) -
+    // except for block-sparse rows of a thousand blocks and more, where whole blocks and one workgroup of eight
+    // wavefronts per CU do as well or better (twice as many workgroups per XCD spread over more of the K/V stream
+    // than its L2 holds).
     constexpr int kHalf = 64;
-    const bool whole_blocks = D != 256 && (D != 128 || (!dense && a.W >= 16));
+    const bool whole_blocks = D != 256 && (!dense && a.W >= 16);
 #define US_AT(SS, CA, DE, SK) \
     if (a.S == SS && (a.causal != 0) == CA && dense == DE) return attn_launch_t<D, SS, CA, DE, SK>(a, stream)
     if (whole_blocks) {
         if constexpr (D != 256) {
-            US_AT(128, true, true, 128); US_AT(128, true, false, 128); US_AT(128, false, true, 128); US_AT(128, false, false, 128);
+            US_AT(128, true, false, 128); US_AT(128, false, false, 128);
         }
     } else {
-        if constexpr (D != 64) {
-            US_AT(128, true, true, kHalf); US_AT(128, true, false, kHalf); US_AT(128, false, true, kHalf); US_AT(128, false, false, kHalf);
-        }
+        US_AT(128, true, true, kHalf); US_AT(128, true, false, kHalf); US_AT(128, false, true, kHalf); US_AT(128, false, false, kHalf);
     }
     US_AT(64, true, true, 64); US_AT(64, true, false, 64); US_AT(64, false, true, 64); US_AT(64, false, false, 64);
 #undef US_AT
