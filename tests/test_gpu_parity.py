@@ -477,6 +477,34 @@ def test_randomised_small_problems(ctx, oracle):
                                  f"mode={mode} param={param} pool={pool} {layout}: {e}") from e
 
 
+@pytest.mark.parametrize("lengths,S,cq,ck,ch,causal", [
+    ((1000, 77, 300), 128, 8, 8, 1, True), ((513, 2049), 128, 8, 8, 1, False), ((700, 131), 64, 4, 16, 2, True),
+    ((333,), 128, 2, 2, 1, True), ((900, 260), 128, 16, 2, 4, False), ((1500,), 64, 8, 8, 1, True)])
+def test_nothing_is_read_from_the_workspace_before_it_is_written(ctx, oracle, lengths, S, cq, ck, ch, causal):
+    """build_mask and sparse_attn_ws leave the same bits whether the workspace held zeros or 0xFF bytes (NaN as
+    floats, -1 as integers) before the call, in both forms of the score computation: every value they read from it
+    they wrote earlier in the same call (rows past a sequence's end, key blocks past a row's valid set and padding
+    included)."""
+    w = W.random_small(H=4, Hkv=2, lengths=lengths, S=S, causal=causal, mode=W.TOP_P, param=0.9, seed=31 + S + cq)
+    w.c_q, w.c_k, w.c_h = cq, ck, ch
+    q, k, v = PU.device_tensors(w)
+    p, s = PU.problem_of(w), PU.select_of(w)
+    for minimal in (False, True):
+        res = []
+        for fill in (0, 255):
+            ws = ctx.alloc_workspace(p, s, minimal=minimal)
+            ws.fill_(fill)
+            m = ctx.alloc_mask(p)
+            m.fill_(-1 if fill else 0)
+            m, sc = ctx.build_mask(p, s, q, k, workspace=ws, mask=m, want_score=True)
+            o, lse = ctx.sparse_attn(p, q, k, v, m, want_lse=True, workspace=ws)
+            torch.cuda.synchronize()
+            res.append((m.clone(), sc.clone(), o.clone(), lse.clone()))
+        for a, b in zip(*res):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), f"minimal={minimal}"
+        assert torch.isfinite(res[0][1]).all()
+
+
 def test_randomised_medium_problems(ctx, oracle):
     """Twenty-four seeded problems of 2K-14K tokens per sequence (many key stages per sweep of the score kernel, several
     workgroups per head, all head dimensions), a third of them with logits that rise, fall, spike or ramp over hundreds
