@@ -82,8 +82,17 @@ hipError_t launch_attention_rank(const AttnArgs &a, const AttnOrder &ord, hipStr
     return hipGetLastError();
 }
 
-hipError_t launch_attention(const AttnArgs &a, hipStream_t stream)
+hipError_t launch_attention(const AttnArgs &a_in, hipStream_t stream)
 {
+    AttnArgs a = a_in;
+    // Dense attention does not depend on the block size (the causal mask is applied per token): problems with
+    // S = 64 run as S = 128, whose workgroups of four wavefronts fill the CUs twice as well as the two of S = 64.
+    if (a.mask == nullptr && a.S == 64) {
+        a.S = 128;
+        a.NQ = 0;
+        for (int b = 0; b < a.st.num_seqs; ++b) a.NQ += (a.st.cu_tok[b + 1] - a.st.cu_tok[b] + 127) / 128;
+        a.W = (a.W + 1) / 2;
+    }
     switch (a.head_dim) {
         case 64: return attn_dispatch_d64(a, stream);
         case 128: return attn_dispatch_d128(a, stream);
