@@ -147,9 +147,17 @@ def main():
     score = torch.empty((p.n_heads_q // s.c_h, p.n_rows, p.n_cols), dtype=torch.float32, device="cuda")
     lay = args.layout
 
-    def step():
+    # HIP events around the dominant kernel's launch inside every step (torch's current stream is the launch stream)
+    ev = []
+
+    def step(timed=False):
         ctx.build_mask(p, s, q, k, lay, workspace=ws, mask=mask)
+        if timed:
+            ev.append(_events(2))
+            ev[-1][0].record()
         ctx.sparse_attn(p, q, k, v, mask, lay, out=o, workspace=ws)      # unisparse_sparse_attn_ws: ranked work order
+        if timed:
+            ev[-1][1].record()
 
     if args.profile_copy_mb > 0:
         src = torch.empty(args.profile_copy_mb << 20, dtype=torch.uint8, device="cuda")
@@ -162,9 +170,10 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        step(timed=True)
     torch.cuda.synchronize()
     ms_step = (time.perf_counter() - t1) * 1e3 / args.steps
+    ms_sparse_in_step = sum(a.elapsed_time(b) for a, b in ev) / len(ev)
 
     # ---- per-kernel timings (HIP events on the launch stream) ------------------------------------
     reps = max(3, args.steps)
@@ -177,7 +186,18 @@ def main():
     _, sc = ctx.build_mask(p, s, q, k, lay, workspace=ws, mask=mask, want_score=True)
     ms_select = _time_ms(lambda: ctx.select_blocks(p, s, sc, mask=mask), reps)
     ms_sparse = _time_ms(lambda: ctx.sparse_attn(p, q, k, v, mask, lay, out=o, workspace=ws), reps)
-    ms_dense = _time_ms(lambda: ctx.full_attn(p, q, k, v, lay, out=od), args.dense_reps, warm=1)
+    # the dense baseline in the same setting as the sparse launch of a step: after the mask kernels, not back to back
+    # with itself (the device clock depends on what ran just before)
+    ctx.full_attn(p, q, k, v, lay, out=od)
+    evd = []
+    for _ in range(args.dense_reps):
+        ctx.build_mask(p, s, q, k, lay, workspace=ws, mask=mask)
+        evd.append(_events(2))
+        evd[-1][0].record()
+        ctx.full_attn(p, q, k, v, lay, out=od)
+        evd[-1][1].record()
+    torch.cuda.synchronize()
+    ms_dense = sum(a.elapsed_time(b) for a, b in evd) / len(evd)
     torch.cuda.synchronize()
 
     m_gpu = api.unpack_mask(mask, p.n_cols)
@@ -185,7 +205,7 @@ def main():
     valid = float(w.valid_pairs() * w.n_heads_q)
     S, d = w.block_size, w.head_dim
     flop_pair = 4.0 * S * S * d
-    sparse_tflops = nnz * flop_pair / (ms_sparse * 1e-3) / 1e12
+    sparse_tflops = nnz * flop_pair / (ms_sparse_in_step * 1e-3) / 1e12      # the launches of the timed steps
     dense_tflops = valid * flop_pair / (ms_dense * 1e-3) / 1e12
     pool_bytes = (w.q.size + w.k.size) * 2 * (1 + 1.0 / s.c_q)
     out = {
@@ -199,10 +219,13 @@ def main():
                    "gain": w.gain, "layout": lay},
         "speedup_vs_dense": ms_dense / ms_step,
         "mask_density": nnz / valid,
-        # (scores_and_select: the one-sweep score kernel plus the selection kernel that normalises its row sums;
-        #  select_given_scores: unisparse_select_blocks alone on a score buffer, for reference)
+        # (sparse_attn: HIP events around the launch inside the timed steps, row ranking included; the other entries
+        #  are timed after them, each launch repeated back to back.  scores_and_select: the one-sweep score kernel plus
+        #  the selection kernel that normalises its row sums; select_given_scores: unisparse_select_blocks alone on a
+        #  score buffer, for reference)
         "kernels_ms": {"pool": ms_pool, "scores_and_select": ms_build - ms_pool, "select_given_scores": ms_select,
-                       "build_mask": ms_build, "sparse_attn": ms_sparse, "dense_attn": ms_dense},
+                       "build_mask": ms_build, "sparse_attn": ms_sparse_in_step, "sparse_attn_back_to_back": ms_sparse,
+                       "dense_attn": ms_dense},
         "effective_tflops": valid * flop_pair / (ms_step * 1e-3) / 1e12,
         "dense_tflops": dense_tflops,
         "pool_gbs": pool_bytes / (ms_pool * 1e-3) / 1e9,
