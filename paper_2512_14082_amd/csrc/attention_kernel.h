@@ -718,7 +718,9 @@ static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
     ord.head_major = 0;
     ord.table = nullptr;
     // ranked order when the caller gave scratch for it; long rows (>= 960 blocks) then do best with chunks of one head
+    // (not for a grid that fits the device at once: there the order changes nothing and the ranking is one more launch)
     const bool ranked = !DENSE && a.sched != nullptr && a.NQ <= kRankMaxRows && a.n_heads_q < 2048 &&
+                        (int64_t)a.n_heads_q * a.NQ > 512 &&
                         (int64_t)attention_sched_bytes(a.n_heads_q, a.n_heads_kv, a.NQ) <= a.sched_bytes;
     if (ranked && a.W >= 16) {
         ord.HG = 1;
