@@ -235,7 +235,8 @@ unisparse_status unisparse_sparse_attn(unisparse_ctx *ctx, const unisparse_probl
  *   workspace : DEVICE scratch of at least unisparse_attn_workspace_bytes(p) bytes (the workspace of a finished
  *               unisparse_build_mask of the same problem is large enough and may be reused); NULL = no ranking,
  *               exactly unisparse_sparse_attn.  UNISPARSE_ERR_WORKSPACE if too small.
- * Problems with more than 8192 query-block rows run in the default order.
+ * Problems with more than 8192 query-block rows, and problems of at most 512 (head, query-block row) pairs - which
+ * the device works on all at once - run in the default order.
  */
 size_t unisparse_attn_workspace_bytes(const unisparse_problem *p);
 unisparse_status unisparse_sparse_attn_ws(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor Q,
@@ -243,7 +244,8 @@ unisparse_status unisparse_sparse_attn_ws(unisparse_ctx *ctx, const unisparse_pr
                                           unisparse_tensor O, float *lse, void *workspace, size_t workspace_bytes,
                                           void *stream);
 
-/* Dense attention (Sec. 2.1): the same kernel visiting every valid block.  The speedup baseline. */
+/* Dense attention (Sec. 2.1): the same kernel visiting every valid block.  The speedup baseline.  (The result does
+ * not depend on block_size, which only has to be a valid one.) */
 unisparse_status unisparse_full_attn(unisparse_ctx *ctx, const unisparse_problem *p, unisparse_tensor Q,
                                      unisparse_tensor K, unisparse_tensor V, unisparse_tensor O, float *lse,
                                      void *stream);
