@@ -8,7 +8,8 @@ hipError_t attn_dispatch_d128(const AttnArgs &a, hipStream_t stream) { return at
 // ---- ranked work order ------------------------------------------------------------------------------------------
 // One workgroup per query head: the head's rows are sorted by (sequence ascending, selected blocks descending, row
 // descending) - a bitonic sort of 32-bit keys in LDS - and the row of rank k is written where the attention kernel's
-// workgroup of chunk slot k % R of row group k / R of this head looks for it.
+// workgroup of chunk slot k % R of row group k / R of this head looks for it.  The chunks are numbered row group by
+// row group with the heads rotated, or (AttnOrder::head_major) key head by key head.
 constexpr int kRankThreads = 1024;
 
 __global__ __launch_bounds__(kRankThreads) void attn_rank_kernel(AttnArgs a, AttnOrder ord, int32_t *table)
@@ -53,7 +54,15 @@ __global__ __launch_bounds__(kRankThreads) void attn_rank_kernel(AttnArgs a, Att
     const int hg = h / ord.HG, hh = h % ord.HG;
     for (int k = tid; k < ord.n_rg * ord.R; k += kRankThreads) {
         const int rg = k / ord.R;
-        const int ci = rg * n_hg + ((hg - rg) % n_hg + n_hg) % n_hg;     // the chunk with (ci % n_hg + rg) % n_hg == hg
+        int ci = rg * n_hg + ((hg - rg) % n_hg + n_hg) % n_hg;     // the chunk with (ci % n_hg + rg) % n_hg == hg
+        if (ord.head_major) {
+            // all chunks of one key head, then the next key head's: positions inside a key head's run ordered by
+            // (row group, head) and shifted cyclically by the key head's number, so that over the key heads every
+            // XCD (position % 8) sees every rank
+            const int gq = (a.n_heads_q / a.n_heads_kv) / ord.HG;        // head groups per key head
+            const int kvg = hg / gq, nph = ord.n_rg * gq;
+            ci = kvg * nph + (rg * gq + hg % gq + kvg) % nph;
+        }
         const int idx = (ci / kNumXcd) * cs + hh * ord.R + k % ord.R;
         const int row = k < a.NQ ? a.NQ - 1 - (int)(keys[k] & 0x1fffu) : -1;
         table[(int64_t)idx * kNumXcd + ci % kNumXcd] = row < 0 ? -1 : ((h << 20) | row);

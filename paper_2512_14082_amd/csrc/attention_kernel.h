@@ -80,16 +80,19 @@ template <int D> __device__ __forceinline__ int v_swizzle(int row) { return D ==
 // Workgroups of a chunk then have about the same length, start together and stay together on their way through the
 // K/V blocks they share, which is what the L2 needs: on the 128K configuration the traffic behind the L2 halves.  The
 // rank table is made by attn_rank_kernel from the mask alone, so the order - and with it nothing but the order: every
-// row's arithmetic is the same - is a function of the mask.
+// row's arithmetic is the same - is a function of the mask.  The 8 chunks that run at a time are 8 consecutive
+// chunks: of one row group and 8 HG heads, or - when the K/V of the key heads those belong to would not fit the
+// 256 MB cache behind the L2s (many key heads, long sequences) - of one key head (head_major).
 struct AttnOrder {
     int R;           // rows per chunk
     int HG;          // query heads (of one key head) per chunk
     int n_rg;        // row groups = ceil(NQ / R)
     int n_chunks;    // n_rg * (n_heads_q / HG)
-    int head_major;  // 1: all row groups of key head 0, then head 1, ... ; 0: row groups outermost, heads rotated
+    int head_major;  // 1: all row groups of key head 0, then key head 1, ... ; 0: row groups outermost, heads rotated
     const int32_t *table;   // ranked variant: (head << 20 | row) per workgroup id, -1 = no work; NULL = formula below
 };
 constexpr int kRankMaxRows = 8192;      // rows per head the rank kernel sorts (in LDS)
+constexpr int64_t kLastLevelCacheBytes = (int64_t)256 << 20;   // MI355X: 256 MB behind the XCDs' L2s
 
 template <int D, int S, bool CAUSAL, bool DENSE, int SKP>
 __global__ __launch_bounds__((AttnCfg<S, D, SKP>::NT))
@@ -731,6 +734,14 @@ static hipError_t attn_launch_t(const AttnArgs &a, hipStream_t stream)
     const int64_t per_xcd = (ord.n_chunks + kNumXcd - 1) / kNumXcd;
     const int64_t nblk = per_xcd * kNumXcd * ord.R * ord.HG;
     if (ranked) {
+        // The 8 chunks that run at a time belong to 8 HG / G key heads.  When the K and V of that many key heads (of
+        // the longest sequence) do not fit the last-level cache, the chunks are ordered key head by key head instead
+        // of row group by row group, so that one key head's K/V is what the XCDs' L2 misses fall on.
+        int max_len = 0;
+        for (int b = 0; b < a.st.num_seqs; ++b) max_len = max(max_len, a.st.cu_tok[b + 1] - a.st.cu_tok[b]);
+        const int64_t kv_at_a_time = min((int64_t)a.n_heads_kv, ((int64_t)kNumXcd * ord.HG + G - 1) / G);
+        const int64_t kv_bytes = kv_at_a_time * 2 * (int64_t)max_len * D * 2;
+        ord.head_major = kv_at_a_time > 1 && kv_bytes >= kLastLevelCacheBytes ? 1 : 0;
         e = launch_attention_rank(a, ord, stream);
         if (e != hipSuccess) return e;
         ord.table = a.sched;
