@@ -406,6 +406,17 @@ def test_ranked_work_order_gives_identical_output(ctx, oracle):
     with pytest.raises(api.UnisparseError) as e:
         ctx.sparse_attn(p, q, k, v, m, workspace=torch.empty(64, dtype=torch.uint8, device="cuda"))
     assert e.value.code == 5
+    # ungrouped heads whose K/V pass the last-level cache eight heads at a time: chunks ordered key head by key head
+    w = W.random_small(H=8, Hkv=8, lengths=(262144,), S=128, causal=True, mode=W.TOP_K, param=0.01, seed=320, d=128)
+    q, k, v = PU.device_tensors(w)
+    p, s = PU.problem_of(w), PU.select_of(w)
+    m, _ = ctx.build_mask(p, s, q, k)
+    ws = torch.empty(ctx.attn_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    o1, l1 = ctx.sparse_attn(p, q, k, v, m, want_lse=True)
+    o2, l2 = ctx.sparse_attn(p, q, k, v, m, want_lse=True, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(l1, l2), "key-head-major order"
+    del q, k, v, o1, o2, w
     # the largest row count that is ranked (8192 rows: the whole sort buffer) and the first that is not
     for nq, lengths in ((8192, (4096 * 64, 4096 * 64)), (8200, (4096 * 64, 4096 * 64, 8 * 64))):
         w = W.random_small(H=1, Hkv=1, lengths=lengths, S=64, causal=True, mode=W.TOP_K, param=0.004, seed=310, d=64)
